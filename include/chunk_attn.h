@@ -1,0 +1,131 @@
+/*
+ * chunk_attn.h -- C ABI of the MI355X (gfx950) chunk-attention library.
+ *
+ * Chunk attention is the attention step of one pipeline stage over one "chunk" of the
+ * paper's Dynamic Pipeline Parallelism (section 3.1, "Definition of Chunk").  A chunk
+ * {C, S} is a set of slice lengths S and a context length C for its first slice:
+ *
+ *   batched (packed) chunk : several whole short sequences, C = 0;
+ *   split chunk            : one slice of a long sequence; its queries also attend to the
+ *                            keys/values of all earlier slices (the context, length C);
+ *   hybrid chunk           : a tail slice with context C packed with whole short sequences.
+ *
+ * Here a chunk is a table of segments.  Segment t has q_len = s query rows and
+ * kv_len = C + s key/value rows.  Query i of the segment (row q_start + i) sits at position
+ * C + i of its sequence and attends to key/value rows kv_start + j for j = 0 .. C + i
+ * (causal mask aligned to the end of the key range; section 2.1: a query accesses only the
+ * keys and values of preceding tokens) and to nothing outside its own segment (section 2.2,
+ * sequence packing: packed sequences do not attend to each other).  The result is exact
+ * softmax attention, O = softmax(scale * Q K^T + mask) V, and its exact gradients; key and
+ * value gradients of context rows are produced too, because the gradient of a token's key
+ * and value depends on every later token (section 2.1; section 3.2.2 on the gradients of
+ * keys and values of split sequences).
+ *
+ * Tensors (all DEVICE pointers, contiguous, bf16 unless noted; the caller owns them):
+ *   q, o, d_o, dq : [total_q ][num_q_heads ][head_dim]
+ *   k, v, dk, dv  : [total_kv][num_kv_heads][head_dim]
+ *   lse           : [num_q_heads][total_q] float32, natural-log sum of exp of the scaled scores
+ * Query head h uses key/value head h / (num_q_heads / num_kv_heads).
+ *
+ * All calls are asynchronous: they enqueue work on `stream` (a hipStream_t passed as
+ * void*; NULL is the default stream) and return.  The segment table is a HOST pointer and
+ * is only read during the call.  The library allocates no device memory: scratch space is
+ * the caller's `workspace` (device memory, 256-byte aligned, at least the size reported by
+ * chunk_attn_workspace_bytes).  Functions return CHUNK_ATTN_OK (0) or a negative code and
+ * never throw or abort; argument errors are detected on the host before anything is
+ * launched.
+ */
+#ifndef CHUNK_ATTN_H_
+#define CHUNK_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CHUNK_ATTN_OK = 0,
+  CHUNK_ATTN_INVALID_ARG = -1,         /* null pointer, non-positive dimension, bad scale */
+  CHUNK_ATTN_UNSUPPORTED = -2,         /* head_dim not 64 or 128, or num_q_heads % num_kv_heads != 0 */
+  CHUNK_ATTN_BAD_SEGMENT = -3,         /* see chunk_attn_desc.segments */
+  CHUNK_ATTN_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes below chunk_attn_workspace_bytes */
+  CHUNK_ATTN_HIP_ERROR = -5            /* a HIP call or kernel launch failed */
+};
+
+/* One segment, in rows.  Context length C = kv_len - q_len >= 0. */
+typedef struct {
+  int32_t q_start, q_len, kv_start, kv_len;
+} chunk_attn_seg;
+
+typedef struct {
+  int32_t num_q_heads;  /* Hq > 0 */
+  int32_t num_kv_heads; /* Hkv > 0, divides Hq */
+  int32_t head_dim;     /* 64 or 128 */
+  int32_t total_q;      /* rows of q / o / d_o / dq */
+  int32_t total_kv;     /* rows of k / v / dk / dv */
+  int32_t num_segments; /* >= 1 */
+  /* HOST array, borrowed for the call.  Requirements (else CHUNK_ATTN_BAD_SEGMENT):
+   * q_len >= 1, kv_len >= q_len, ranges inside [0,total_q) resp. [0,total_kv); query
+   * ranges in increasing order, back to back, covering [0,total_q) exactly; key ranges
+   * in increasing order without overlap (gaps are allowed). */
+  const chunk_attn_seg* segments;
+  float softmax_scale; /* finite, > 0; normally 1/sqrt(head_dim) */
+} chunk_attn_desc;
+
+/*
+ * Scratch sizes (bytes) for a descriptor: *fwd_bytes for chunk_attn_fwd, *bwd_bytes for
+ * chunk_attn_bwd (the latter holds the float32 dQ accumulator, the row sums
+ * D_i = <dO_i, O_i>, float32 dK/dV staging when accumulate_dkv is used, and the tile
+ * schedule).  Either output pointer may be NULL.  Validates the descriptor.
+ */
+int chunk_attn_workspace_bytes(const chunk_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
+
+/*
+ * Validates a descriptor on the host without touching the GPU (same checks every entry
+ * point performs first).
+ */
+int chunk_attn_validate(const chunk_attn_desc* desc);
+
+/*
+ * Forward (paper section 3.1 mask; exact softmax attention, section 3.2.2 notes that
+ * no O(S^2) score matrix is materialised).  Writes o (bf16) and lse (float32) for every
+ * query row.  q, k, v are read only.
+ */
+int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward for the loss L = sum(o .* d_o): dq for every query row; dk, dv for every
+ * key/value row including context rows (section 2.1: gradients of a token's key and value
+ * come from the tokens after it).  o and lse must be the outputs of chunk_attn_fwd on the
+ * same inputs.
+ *
+ * accumulate_dkv == 0: dk/dv rows inside some segment's key range are overwritten, all
+ *   other rows are set to zero.
+ * accumulate_dkv != 0: rows inside a key range get  dk[row] = bf16(float(dk[row]) + sum)
+ *   (one rounding per call), other rows are left untouched.  This is how the slices of a
+ *   split sequence, run in reverse order, add up the gradients of shared context rows
+ *   (section 3.2.2: the key/value gradients of all slices stay alive until each slice's
+ *   own backward has run).
+ */
+int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                   const void* d_o, const float* lse, void* dq, void* dk, void* dv, int accumulate_dkv,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Number of unmasked (query, key) pairs per query head, sum_t (s C + s (s + 1) / 2): the
+ * quantity behind the quadratic term of the paper's computation-time model (Eq. 1).
+ * Forward costs 4 * head_dim flops per pair per query head, backward 10 * head_dim.
+ * Returns a negative error code for an invalid descriptor.
+ */
+int64_t chunk_attn_pair_count(const chunk_attn_desc* desc);
+
+/* Static description of an error code; for CHUNK_ATTN_HIP_ERROR includes the last HIP error text. */
+const char* chunk_attn_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHUNK_ATTN_H_ */

@@ -1,0 +1,153 @@
+"""Python binding of libchunk_attn.so, the MI355X chunk-attention library.
+
+Argument marshalling only: every step of the computation runs in the library's HIP kernels.
+The functions mirror the C ABI in include/chunk_attn.h (same names).  PyTorch is used for
+device memory and streams; tensors must be contiguous bf16 (float32 for lse) on the GPU.
+There is no CPU fallback: if the library is missing, importing fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libchunk_attn.so")
+
+OK, INVALID_ARG, UNSUPPORTED, BAD_SEGMENT, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, -1, -2, -3, -4, -5
+
+
+class Seg(ctypes.Structure):
+    _fields_ = [("q_start", ctypes.c_int32), ("q_len", ctypes.c_int32),
+                ("kv_start", ctypes.c_int32), ("kv_len", ctypes.c_int32)]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("total_q", ctypes.c_int32), ("total_kv", ctypes.c_int32), ("num_segments", ctypes.c_int32),
+                ("segments", ctypes.POINTER(Seg)), ("softmax_scale", ctypes.c_float)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_21275_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    dp = ctypes.POINTER(Desc)
+    lib.chunk_attn_validate.argtypes = [dp]
+    lib.chunk_attn_validate.restype = ctypes.c_int
+    lib.chunk_attn_pair_count.argtypes = [dp]
+    lib.chunk_attn_pair_count.restype = ctypes.c_int64
+    lib.chunk_attn_strerror.argtypes = [ctypes.c_int]
+    lib.chunk_attn_strerror.restype = ctypes.c_char_p
+    lib.chunk_attn_workspace_bytes.argtypes = [dp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.chunk_attn_workspace_bytes.restype = ctypes.c_int
+    lib.chunk_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.chunk_attn_fwd.restype = ctypes.c_int
+    lib.chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
+    lib.chunk_attn_bwd.restype = ctypes.c_int
+    return lib
+
+
+class _Lazy:
+    """Loads the library on first use so that `python -m paper_2509_21275_amd.build` can run before it exists."""
+    _real = None
+
+    def __getattr__(self, name):
+        if _Lazy._real is None:
+            _Lazy._real = _load()
+        return getattr(_Lazy._real, name)
+
+
+_lib = _Lazy()
+
+
+class ChunkAttnError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__(f"chunk_attn error {code}: {_lib.chunk_attn_strerror(code).decode()}")
+
+
+def make_desc(segs, num_q_heads, num_kv_heads, head_dim, total_q, total_kv, softmax_scale):
+    """Builds a chunk_attn_desc; keep the returned object alive for the duration of the call."""
+    arr = (Seg * max(1, len(segs)))(*[Seg(*[int(x) for x in s]) for s in segs])
+    d = Desc(num_q_heads, num_kv_heads, head_dim, total_q, total_kv, len(segs), arr, float(softmax_scale))
+    d._keepalive = arr
+    return d
+
+
+def chunk_attn_validate(desc) -> int:
+    return _lib.chunk_attn_validate(ctypes.byref(desc))
+
+
+def chunk_attn_strerror(code: int) -> str:
+    return _lib.chunk_attn_strerror(code).decode()
+
+
+def chunk_attn_pair_count(desc) -> int:
+    n = _lib.chunk_attn_pair_count(ctypes.byref(desc))
+    if n < 0:
+        raise ChunkAttnError(int(n))
+    return int(n)
+
+
+def chunk_attn_workspace_bytes(desc):
+    f, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    rc = _lib.chunk_attn_workspace_bytes(ctypes.byref(desc), ctypes.byref(f), ctypes.byref(b))
+    if rc != OK:
+        raise ChunkAttnError(rc)
+    return f.value, b.value
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _check(t, dtype, shape, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype
+            and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name}: expected contiguous {dtype} GPU tensor of shape {tuple(shape)}")
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def chunk_attn_fwd(desc, q, k, v, o, lse, workspace, stream=None) -> None:
+    """Enqueues the forward on `stream` (default: torch's current stream).  Writes o and lse."""
+    import torch
+    qs = (desc.total_q, desc.num_q_heads, desc.head_dim)
+    ks = (desc.total_kv, desc.num_kv_heads, desc.head_dim)
+    _check(q, torch.bfloat16, qs, "q"); _check(k, torch.bfloat16, ks, "k"); _check(v, torch.bfloat16, ks, "v")
+    _check(o, torch.bfloat16, qs, "o"); _check(lse, torch.float32, (desc.num_q_heads, desc.total_q), "lse")
+    rc = _lib.chunk_attn_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(workspace),
+                             workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != OK:
+        raise ChunkAttnError(rc)
+
+
+def chunk_attn_bwd(desc, q, k, v, o, d_o, lse, dq, dk, dv, accumulate_dkv, workspace, stream=None) -> None:
+    """Enqueues the backward on `stream`.  Writes dq; writes or accumulates into dk, dv."""
+    import torch
+    qs = (desc.total_q, desc.num_q_heads, desc.head_dim)
+    ks = (desc.total_kv, desc.num_kv_heads, desc.head_dim)
+    for t, n in ((q, "q"), (o, "o"), (d_o, "d_o"), (dq, "dq")):
+        _check(t, torch.bfloat16, qs, n)
+    for t, n in ((k, "k"), (v, "v"), (dk, "dk"), (dv, "dv")):
+        _check(t, torch.bfloat16, ks, n)
+    _check(lse, torch.float32, (desc.num_q_heads, desc.total_q), "lse")
+    rc = _lib.chunk_attn_bwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
+                             _ptr(dk), _ptr(dv), int(bool(accumulate_dkv)), _ptr(workspace),
+                             workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != OK:
+        raise ChunkAttnError(rc)
+
+
+def alloc_workspace(desc, device="cuda"):
+    """A uint8 tensor large enough for both chunk_attn_fwd and chunk_attn_bwd on this descriptor."""
+    import torch
+    f, b = chunk_attn_workspace_bytes(desc)
+    return torch.empty(max(f, b, 256), dtype=torch.uint8, device=device)

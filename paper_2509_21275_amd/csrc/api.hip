@@ -1,0 +1,208 @@
+// C ABI of the chunk-attention library (include/chunk_attn.h): argument checks, workspace carving,
+// schedule upload and kernel launches.  No device memory is allocated here; the only memory the
+// library owns is a small ring of pinned host buffers through which tile schedules are uploaded.
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+
+#include "kernels.hpp"
+
+using namespace chunk_attn;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+thread_local std::string g_last_hip_error;
+
+int hip_fail(hipError_t e, const char* what) {
+  g_last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return CHUNK_ATTN_HIP_ERROR;
+}
+
+// Pinned staging ring.  A slot is reused only after the copy that read it has completed.
+struct StagingRing {
+  static constexpr int kSlots = 16;
+  struct Slot {
+    void* host = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool in_flight = false;
+  } slots[kSlots];
+  int next = 0;
+  std::mutex mu;
+
+  // Copies `bytes` from src into pinned memory and enqueues the upload to `dst` on `stream`.
+  hipError_t upload(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+    std::lock_guard<std::mutex> lock(mu);
+    Slot& s = slots[next];
+    next = (next + 1) % kSlots;
+    hipError_t e;
+    if (s.in_flight) {
+      if ((e = hipEventSynchronize(s.ev)) != hipSuccess) return e;
+      s.in_flight = false;
+    }
+    if (s.cap < bytes) {
+      if (s.host) {
+        if ((e = hipHostFree(s.host)) != hipSuccess) return e;
+        s.host = nullptr;
+        s.cap = 0;
+      }
+      const size_t cap = std::max<size_t>(align_up(bytes), 1 << 16);
+      if ((e = hipHostMalloc(&s.host, cap, hipHostMallocDefault)) != hipSuccess) return e;
+      s.cap = cap;
+    }
+    if (!s.ev && (e = hipEventCreateWithFlags(&s.ev, hipEventDisableTiming)) != hipSuccess) return e;
+    std::memcpy(s.host, src, bytes);
+    if ((e = hipMemcpyAsync(dst, s.host, bytes, hipMemcpyHostToDevice, stream)) != hipSuccess) return e;
+    if ((e = hipEventRecord(s.ev, stream)) != hipSuccess) return e;
+    s.in_flight = true;
+    return hipSuccess;
+  }
+};
+StagingRing g_ring;
+
+// Which forward variant to run: NQ = 32-row query blocks per wave.
+int fwd_nq(const chunk_attn_desc* d) {
+  (void)d;
+  static int forced = -1;
+  if (forced < 0) {
+    const char* e = std::getenv("CHUNK_ATTN_FWD_NQ");
+    forced = e ? std::atoi(e) : 0;
+  }
+  if (forced == 1 || forced == 2) return forced;
+  return 2;
+}
+
+struct FwdLayout {
+  int nq, tile_rows;
+  size_t items_off, total;
+  std::vector<FwdItem> items;
+};
+
+void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_items) {
+  L.nq = fwd_nq(d);
+  const int group = d->num_q_heads / d->num_kv_heads;
+  L.tile_rows = fwd_tile_rows(group, L.nq);
+  size_t n_items;
+  if (with_items) {
+    L.items = plan_fwd(d, L.tile_rows);
+    n_items = L.items.size();
+  } else {
+    n_items = 0;
+    for (int t = 0; t < d->num_segments; ++t) n_items += (d->segments[t].q_len + L.tile_rows - 1) / L.tile_rows;
+  }
+  L.items_off = 0;
+  L.total = align_up(n_items * sizeof(FwdItem));
+}
+
+}  // namespace
+
+extern "C" {
+
+int chunk_attn_validate(const chunk_attn_desc* desc) { return validate(desc); }
+
+int64_t chunk_attn_pair_count(const chunk_attn_desc* desc) {
+  const int rc = validate(desc);
+  if (rc != CHUNK_ATTN_OK) return rc;
+  return pair_count(desc);
+}
+
+const char* chunk_attn_strerror(int code) {
+  switch (code) {
+    case CHUNK_ATTN_OK: return "ok";
+    case CHUNK_ATTN_INVALID_ARG: return "invalid argument (null pointer, non-positive size or bad scale)";
+    case CHUNK_ATTN_UNSUPPORTED: return "unsupported shape (head_dim must be 64 or 128; num_kv_heads must divide num_q_heads)";
+    case CHUNK_ATTN_BAD_SEGMENT: return "bad segment table";
+    case CHUNK_ATTN_WORKSPACE_TOO_SMALL: return "workspace too small (see chunk_attn_workspace_bytes)";
+    case CHUNK_ATTN_HIP_ERROR: {
+      static thread_local std::string msg;
+      msg = "HIP error: " + g_last_hip_error;
+      return msg.c_str();
+    }
+    default: return "unknown error code";
+  }
+}
+
+int chunk_attn_workspace_bytes(const chunk_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes) {
+  const int rc = validate(desc);
+  if (rc != CHUNK_ATTN_OK) return rc;
+  if (fwd_bytes) {
+    FwdLayout L;
+    layout_fwd(desc, L, false);
+    *fwd_bytes = L.total;
+  }
+  if (bwd_bytes) *bwd_bytes = bwd_workspace_bytes(desc);
+  return CHUNK_ATTN_OK;
+}
+
+int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse,
+                   void* workspace, size_t workspace_bytes, void* stream_v) {
+  const int rc = validate(desc);
+  if (rc != CHUNK_ATTN_OK) return rc;
+  if (!q || !k || !v || !o || !lse || !workspace) return CHUNK_ATTN_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return CHUNK_ATTN_INVALID_ARG;
+  FwdLayout L;
+  layout_fwd(desc, L, true);
+  if (workspace_bytes < L.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  char* ws = static_cast<char*>(workspace);
+
+  hipError_t e = g_ring.upload(ws + L.items_off, L.items.data(), L.items.size() * sizeof(FwdItem), stream);
+  if (e != hipSuccess) return hip_fail(e, "schedule upload");
+
+  FwdParams p;
+  p.q = static_cast<const __bf16*>(q);
+  p.k = static_cast<const __bf16*>(k);
+  p.v = static_cast<const __bf16*>(v);
+  p.o = static_cast<__bf16*>(o);
+  p.lse = lse;
+  p.items = reinterpret_cast<const FwdItem*>(ws + L.items_off);
+  p.num_q_heads = desc->num_q_heads;
+  p.num_kv_heads = desc->num_kv_heads;
+  p.group = desc->num_q_heads / desc->num_kv_heads;
+  p.heads_per_wg = fwd_heads_per_wg(p.group);
+  p.head_splits = p.group / p.heads_per_wg;
+  p.total_q = desc->total_q;
+  p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
+  const int64_t blocks = (int64_t)L.items.size() * p.num_kv_heads * p.head_splits;
+  if (blocks > 0x7fffffff) return CHUNK_ATTN_UNSUPPORTED;
+  e = launch_fwd(p, desc->head_dim, L.nq, (int)blocks, stream);
+  if (e != hipSuccess) return hip_fail(e, "forward launch");
+  return CHUNK_ATTN_OK;
+}
+
+int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                   const void* d_o, const float* lse, void* dq, void* dk, void* dv, int accumulate_dkv,
+                   void* workspace, size_t workspace_bytes, void* stream_v) {
+  const int rc = validate(desc);
+  if (rc != CHUNK_ATTN_OK) return rc;
+  if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return CHUNK_ATTN_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return CHUNK_ATTN_INVALID_ARG;
+  if (workspace_bytes < bwd_workspace_bytes(desc)) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  BwdArgs a;
+  a.q = static_cast<const __bf16*>(q);
+  a.k = static_cast<const __bf16*>(k);
+  a.v = static_cast<const __bf16*>(v);
+  a.o = static_cast<const __bf16*>(o);
+  a.d_o = static_cast<const __bf16*>(d_o);
+  a.lse = lse;
+  a.dq = static_cast<__bf16*>(dq);
+  a.dk = static_cast<__bf16*>(dk);
+  a.dv = static_cast<__bf16*>(dv);
+  a.accumulate = accumulate_dkv != 0;
+  a.workspace = static_cast<char*>(workspace);
+  std::vector<BwdItem> items;
+  size_t items_off = 0;
+  bwd_prepare(desc, items, &items_off);
+  hipError_t e = g_ring.upload(a.workspace + items_off, items.data(), items.size() * sizeof(BwdItem), stream);
+  if (e != hipSuccess) return hip_fail(e, "schedule upload");
+  e = launch_bwd(desc, a, items, stream);
+  if (e != hipSuccess) return hip_fail(e, "backward launch");
+  return CHUNK_ATTN_OK;
+}
+
+}  // extern "C"

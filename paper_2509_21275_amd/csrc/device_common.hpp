@@ -1,0 +1,83 @@
+// Device-side building blocks shared by the chunk-attention kernels (gfx950 only).
+//
+// MFMA v_mfma_f32_32x32x16_bf16 operand layout (wave of 64 lanes, l32 = lane % 32, hh = lane / 32):
+//   A (32 x 16): lane holds A[row = l32][k = 8 hh .. 8 hh + 7]
+//   B (16 x 32): lane holds B[k = 8 hh .. 8 hh + 7][col = l32]
+//   C (32 x 32): lane holds C[row = 8 g + 4 hh + r][col = l32] in acc[4 g + r], g, r = 0..3
+// The k slots of A and B only have to agree with each other, which lets an accumulator
+// tile be fed straight back as a B operand: slot e of half hh in k-step s then stands for
+// contraction index 16 s + 8 (e / 4) + 4 hh + (e % 4)   ("C-order"), and the matching A
+// operand is gathered in that order with the LDS transpose read below.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace chunk_attn {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// value of the lane 32 away
+__device__ __forceinline__ float other_half(float x) {
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  // lanes < 32 hold {own, partner} in {r0, r1}; lanes >= 32 hold {partner, own}
+  return (threadIdx.x & 32) ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float max_halves(float x) {
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_halves(float x) {
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Pack 8 floats to bf16 (round to nearest even, hardware conversion).
+__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, float a4, float a5, float a6,
+                                        float a7) {
+  bf16x8 r;
+  r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+  r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
+  return r;
+}
+__device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) {
+  bf16x4 r;
+  r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+  return r;
+}
+
+// LDS transpose read (ds_read_b64_tr_b16).  Inside each group of 16 lanes, lane i receives,
+// for e = 0..3, 16-bit element (i % 4) of the 8 bytes addressed by lane (i / 4 + 4 e) of the group.
+__device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
+}
+
+// A operand (32 rows x 16 k) in C-order taken from a row-major LDS tile T[k][m] (k = contraction index
+// along LDS rows, m = operand row along LDS columns): returns T[k0 + 8 (e/4) + 4 hh + e%4][m0 + l32], e = 0..7.
+// `stride` is the LDS row pitch in elements.
+__device__ __forceinline__ bf16x8 lds_a_operand_transposed(const __bf16* tile, int stride, int k0, int m0, int lane) {
+  const int hh = lane >> 5;
+  const int row = k0 + 4 * hh + ((lane & 15) >> 2);
+  const int col = m0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const __bf16* p = tile + row * stride + col;
+  s16x4 lo = lds_read_tr(p);
+  s16x4 hi = lds_read_tr(p + 8 * stride);
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+}  // namespace chunk_attn

@@ -1,0 +1,94 @@
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cmath>
+
+namespace chunk_attn {
+
+int validate(const chunk_attn_desc* d) {
+  if (!d || !d->segments) return CHUNK_ATTN_INVALID_ARG;
+  if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->head_dim <= 0 || d->total_q <= 0 || d->total_kv <= 0 ||
+      d->num_segments <= 0)
+    return CHUNK_ATTN_INVALID_ARG;
+  if (!(d->softmax_scale > 0.0f) || !std::isfinite(d->softmax_scale)) return CHUNK_ATTN_INVALID_ARG;
+  if (d->head_dim != 64 && d->head_dim != 128) return CHUNK_ATTN_UNSUPPORTED;
+  if (d->num_q_heads % d->num_kv_heads != 0) return CHUNK_ATTN_UNSUPPORTED;
+  int64_t q_next = 0, kv_next = 0;
+  for (int t = 0; t < d->num_segments; ++t) {
+    const chunk_attn_seg& s = d->segments[t];
+    if (s.q_len < 1 || s.kv_len < s.q_len) return CHUNK_ATTN_BAD_SEGMENT;
+    if (s.q_start != q_next) return CHUNK_ATTN_BAD_SEGMENT;  // in order, back to back, from row 0
+    if (s.kv_start < kv_next) return CHUNK_ATTN_BAD_SEGMENT; // in order, no overlap
+    q_next = (int64_t)s.q_start + s.q_len;
+    kv_next = (int64_t)s.kv_start + s.kv_len;
+    if (q_next > d->total_q || kv_next > d->total_kv) return CHUNK_ATTN_BAD_SEGMENT;
+  }
+  if (q_next != d->total_q) return CHUNK_ATTN_BAD_SEGMENT;
+  return CHUNK_ATTN_OK;
+}
+
+int64_t pair_count(const chunk_attn_desc* d) {
+  int64_t n = 0;
+  for (int t = 0; t < d->num_segments; ++t) {
+    const int64_t s = d->segments[t].q_len, C = (int64_t)d->segments[t].kv_len - s;
+    n += s * C + s * (s + 1) / 2;
+  }
+  return n;
+}
+
+std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows) {
+  std::vector<FwdItem> items;
+  for (int t = 0; t < d->num_segments; ++t) {
+    const chunk_attn_seg& s = d->segments[t];
+    const int32_t C = s.kv_len - s.q_len;
+    for (int32_t i0 = 0; i0 < s.q_len; i0 += tile_rows) {
+      FwdItem it;
+      it.q_row0 = s.q_start + i0;
+      it.q_rows = std::min<int32_t>(tile_rows, s.q_len - i0);
+      it.kv_row0 = s.kv_start;
+      it.n0 = C + i0 + 1;
+      items.push_back(it);
+    }
+  }
+  // most keys first, so the long items start early and the short ones fill the tail
+  std::stable_sort(items.begin(), items.end(), [](const FwdItem& a, const FwdItem& b) {
+    return (int64_t)a.n0 + a.q_rows > (int64_t)b.n0 + b.q_rows;
+  });
+  return items;
+}
+
+std::vector<BwdItem> plan_bwd(const chunk_attn_desc* d, int tile_rows) {
+  std::vector<BwdItem> items;
+  for (int t = 0; t < d->num_segments; ++t) {
+    const chunk_attn_seg& s = d->segments[t];
+    const int32_t C = s.kv_len - s.q_len;
+    for (int32_t j0 = 0; j0 < s.kv_len; j0 += tile_rows) {
+      BwdItem it{};
+      it.kv_row0 = s.kv_start + j0;
+      it.kv_rows = std::min<int32_t>(tile_rows, s.kv_len - j0);
+      const int32_t i_first = std::max<int32_t>(0, j0 - C);  // first query that sees key j0
+      it.q_row0 = s.q_start + i_first;
+      it.q_rows = s.q_len - i_first;
+      it.n0 = C + i_first + 1;
+      it.j0 = j0;
+      items.push_back(it);
+    }
+  }
+  std::stable_sort(items.begin(), items.end(),
+                   [](const BwdItem& a, const BwdItem& b) { return a.q_rows > b.q_rows; });
+  return items;
+}
+
+std::vector<std::pair<int32_t, int32_t>> uncovered_kv_ranges(const chunk_attn_desc* d) {
+  std::vector<std::pair<int32_t, int32_t>> gaps;
+  int32_t next = 0;
+  for (int t = 0; t < d->num_segments; ++t) {
+    const chunk_attn_seg& s = d->segments[t];
+    if (s.kv_start > next) gaps.push_back({next, s.kv_start});
+    next = s.kv_start + s.kv_len;
+  }
+  if (next < d->total_kv) gaps.push_back({next, d->total_kv});
+  return gaps;
+}
+
+}  // namespace chunk_attn

@@ -1,0 +1,75 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU fp64 oracle, element by element.
+
+Tolerances (max-abs error relative to the tensor's max magnitude): 2e-2 for O, 5e-2 for dQ, dK, dV.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from gpu_util import TOL_GRAD, TOL_O, make_inputs, rel_err, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def full_compare(oracle_mod, case, scale=None):
+    q, k, v, do = make_inputs(case)
+    o, lse, dq, dk, dv = run_gpu(case, q, k, v, do, scale=scale)
+    orc = oracle_mod.Oracle(case.segs, q.cpu(), k.cpu(), v.cpu(), do.cpu(), scale if scale is not None else case.scale)
+    O, LSE = orc.forward()
+    dQ, dK, dV = orc.backward()
+    errs = {"o": rel_err(o, O), "dq": rel_err(dq, dQ), "dk": rel_err(dk, dK), "dv": rel_err(dv, dV),
+            "lse_abs": float(np.abs(lse.double().cpu().numpy() - LSE).max())}
+    print(case.name, errs, flush=True)
+    assert errs["o"] <= TOL_O and errs["lse_abs"] <= 2e-2
+    assert errs["dq"] <= TOL_GRAD and errs["dk"] <= TOL_GRAD and errs["dv"] <= TOL_GRAD
+    return errs
+
+
+def test_config1_packed_full(oracle_mod):
+    full_compare(oracle_mod, synth.case_by_index(1))
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_scaled_replicas_full(oracle_mod, idx):
+    full_compare(oracle_mod, synth.scaled_case(idx, 16))
+
+
+EDGE = [
+    # name, segs, Hq, Hkv, d
+    ("one_token", [(0, 1, 0, 1)], 4, 4, 64),
+    ("one_query_long_context", [(0, 1, 0, 700)], 8, 2, 128),
+    ("ragged_single", [(0, 77, 0, 77)], 4, 1, 128),
+    ("ragged_tail_slice", [(0, 130, 0, 1000)], 8, 2, 128),
+    ("context_not_tile_aligned", [(0, 200, 0, 200 + 333)], 8, 8, 64),
+    ("many_tiny", [(i, 1, 3 * i, 1) for i in range(40)], 4, 2, 64),
+    ("hybrid_with_gaps", [(0, 150, 5, 400), (150, 70, 420, 70), (220, 1, 500, 1), (221, 300, 512, 300)], 8, 2, 128),
+    ("mha_g1_d128", [(0, 300, 0, 300), (300, 260, 300, 260)], 3, 3, 128),
+    ("gqa2", [(0, 129, 0, 257)], 4, 2, 128),
+    ("gqa8", [(0, 96, 0, 640), (96, 160, 640, 160)], 16, 2, 128),
+    ("gqa3_odd_group", [(0, 65, 0, 193)], 6, 2, 64),
+]
+
+
+@pytest.mark.parametrize("name,segs,Hq,Hkv,d", EDGE, ids=[e[0] for e in EDGE])
+def test_edge_cases(oracle_mod, name, segs, Hq, Hkv, d):
+    tq = max(s[0] + s[1] for s in segs)
+    tkv = max(s[2] + s[3] for s in segs) + 3          # trailing key rows that no segment covers
+    case = synth.ChunkCase(name, [synth.Seg(*s) for s in segs], tq, tkv, Hq, Hkv, d, 4242 + len(name))
+    q, k, v, do = make_inputs(case)
+    o, lse, dq, dk, dv = run_gpu(case, q, k, v, do)
+    orc = oracle_mod.Oracle(case.segs, q.cpu(), k.cpu(), v.cpu(), do.cpu(), case.scale)
+    O, LSE = orc.forward(); dQ, dK, dV = orc.backward()
+    errs = (rel_err(o, O), rel_err(dq, dQ), rel_err(dk, dK), rel_err(dv, dV))
+    print(name, errs, flush=True)
+    assert errs[0] <= TOL_O and max(errs[1:]) <= TOL_GRAD
+    # rows outside every key range get exactly zero
+    cov = np.zeros(tkv, dtype=bool)
+    for s in segs:
+        cov[s[2]:s[2] + s[3]] = True
+    assert torch.all(dk.cpu()[~cov] == 0) and torch.all(dv.cpu()[~cov] == 0)
+
+
+def test_nonstandard_scale(oracle_mod):
+    case = synth.ChunkCase("scale", synth.hybrid_chunk(100, 300, [50, 90]), 240, 540, 8, 2, 128, 99)
+    full_compare(oracle_mod, case, scale=0.05)
