@@ -122,6 +122,15 @@ int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, co
  */
 int64_t chunk_attn_pair_count(const chunk_attn_desc* desc);
 
+/*
+ * Measurement hook (not part of the method): arms one pair of hipEvent_t (passed as void*) for the
+ * calling thread.  The next chunk_attn_fwd or chunk_attn_bwd call on this thread records `start`
+ * immediately before and `stop` immediately after its main kernel (the forward kernel, resp. the
+ * dK/dV/dQ kernel of the backward) on that call's stream, then disarms.  Pass NULLs to disarm.
+ * The caller owns the events.  Always returns CHUNK_ATTN_OK.
+ */
+int chunk_attn_profile_events(void* start_event, void* stop_event);
+
 /* Static description of an error code; for CHUNK_ATTN_HIP_ERROR includes the last HIP error text. */
 const char* chunk_attn_strerror(int code);
 

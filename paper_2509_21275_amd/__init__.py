@@ -46,6 +46,8 @@ def _load():
     lib.chunk_attn_fwd.restype = ctypes.c_int
     lib.chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
     lib.chunk_attn_bwd.restype = ctypes.c_int
+    lib.chunk_attn_profile_events.argtypes = [vp, vp]
+    lib.chunk_attn_profile_events.restype = ctypes.c_int
     return lib
 
 
@@ -144,6 +146,45 @@ def chunk_attn_bwd(desc, q, k, v, o, d_o, lse, dq, dk, dv, accumulate_dkv, works
                              workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != OK:
         raise ChunkAttnError(rc)
+
+
+def chunk_attn_profile_events(start_event, stop_event) -> None:
+    """Arms raw hipEvent_t handles (ints or None) for the next forward/backward call of this thread."""
+    _lib.chunk_attn_profile_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))
+
+
+class HipEvents:
+    """A pool of raw hipEvent_t pairs (timing enabled) created through the HIP runtime, for kernel timing."""
+
+    def __init__(self):
+        self._hip = ctypes.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self._all = []
+
+    def pair(self):
+        evs = []
+        for _ in range(2):
+            e = ctypes.c_void_p()
+            rc = self._hip.hipEventCreate(ctypes.byref(e))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            evs.append(e.value)
+        self._all.extend(evs)
+        return tuple(evs)
+
+    def elapsed_ms(self, start, stop) -> float:
+        ms = ctypes.c_float()
+        rc = self._hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(start), ctypes.c_void_p(stop))
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return ms.value
+
+    def close(self):
+        for e in self._all:
+            self._hip.hipEventDestroy(ctypes.c_void_p(e))
+        self._all = []
 
 
 def alloc_workspace(desc, device="cuda"):

@@ -64,43 +64,50 @@ struct StagingRing {
 };
 StagingRing g_ring;
 
-// Which forward variant to run: NQ = 32-row query blocks per wave.
-int fwd_nq(const chunk_attn_desc* d) {
-  (void)d;
-  static int forced = -1;
-  if (forced < 0) {
-    const char* e = std::getenv("CHUNK_ATTN_FWD_NQ");
-    forced = e ? std::atoi(e) : 0;
-  }
-  if (forced == 1 || forced == 2) return forced;
-  return 2;
-}
-
+// Forward workspace: [work items | transpose jobs] (uploaded as one blob) then the transposed V images.
 struct FwdLayout {
-  int nq, tile_rows;
-  size_t items_off, total;
+  int tile_rows;
+  size_t items_bytes, jobs_off, blob_bytes, vt_off, total;
+  int64_t kv_tiles;
   std::vector<FwdItem> items;
+  std::vector<TileJob> jobs;
 };
 
-void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_items) {
-  L.nq = fwd_nq(d);
+void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_plan) {
   const int group = d->num_q_heads / d->num_kv_heads;
-  L.tile_rows = fwd_tile_rows(group, L.nq);
-  size_t n_items;
-  if (with_items) {
+  L.tile_rows = fwd_tile_rows(group);
+  size_t n_items = 0;
+  if (with_plan) {
     L.items = plan_fwd(d, L.tile_rows);
+    L.jobs = tile_jobs(d, true, nullptr);
     n_items = L.items.size();
   } else {
-    n_items = 0;
     for (int t = 0; t < d->num_segments; ++t) n_items += (d->segments[t].q_len + L.tile_rows - 1) / L.tile_rows;
   }
-  L.items_off = 0;
-  L.total = align_up(n_items * sizeof(FwdItem));
+  L.kv_tiles = count_tiles(d, true);
+  L.items_bytes = n_items * sizeof(FwdItem);
+  L.jobs_off = align_up(L.items_bytes);
+  L.blob_bytes = L.jobs_off + (size_t)L.kv_tiles * sizeof(TileJob);
+  L.vt_off = align_up(L.blob_bytes);
+  L.total = L.vt_off + align_up((size_t)L.kv_tiles * d->num_kv_heads * d->head_dim * 64 * sizeof(__bf16));
 }
 
 }  // namespace
 
+namespace chunk_attn {
+ProfileEvents& profile_events() {
+  static thread_local ProfileEvents ev;
+  return ev;
+}
+}  // namespace chunk_attn
+
 extern "C" {
+
+int chunk_attn_profile_events(void* start_event, void* stop_event) {
+  profile_events().start = static_cast<hipEvent_t>(start_event);
+  profile_events().stop = static_cast<hipEvent_t>(stop_event);
+  return CHUNK_ATTN_OK;
+}
 
 int chunk_attn_validate(const chunk_attn_desc* desc) { return validate(desc); }
 
@@ -150,8 +157,15 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   char* ws = static_cast<char*>(workspace);
 
-  hipError_t e = g_ring.upload(ws + L.items_off, L.items.data(), L.items.size() * sizeof(FwdItem), stream);
+  std::vector<char> blob(L.blob_bytes);
+  std::memcpy(blob.data(), L.items.data(), L.items_bytes);
+  std::memcpy(blob.data() + L.jobs_off, L.jobs.data(), L.jobs.size() * sizeof(TileJob));
+  hipError_t e = g_ring.upload(ws, blob.data(), blob.size(), stream);
   if (e != hipSuccess) return hip_fail(e, "schedule upload");
+  __bf16* vt = reinterpret_cast<__bf16*>(ws + L.vt_off);
+  e = launch_transpose(static_cast<const __bf16*>(v), desc->num_kv_heads, desc->head_dim,
+                       reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.jobs.size(), L.kv_tiles, vt, stream);
+  if (e != hipSuccess) return hip_fail(e, "transpose launch");
 
   FwdParams p;
   p.q = static_cast<const __bf16*>(q);
@@ -159,7 +173,9 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   p.v = static_cast<const __bf16*>(v);
   p.o = static_cast<__bf16*>(o);
   p.lse = lse;
-  p.items = reinterpret_cast<const FwdItem*>(ws + L.items_off);
+  p.vt = vt;
+  p.items = reinterpret_cast<const FwdItem*>(ws);
+  p.total_kv_tiles = L.kv_tiles;
   p.num_q_heads = desc->num_q_heads;
   p.num_kv_heads = desc->num_kv_heads;
   p.group = desc->num_q_heads / desc->num_kv_heads;
@@ -169,8 +185,12 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
   const int64_t blocks = (int64_t)L.items.size() * p.num_kv_heads * p.head_splits;
   if (blocks > 0x7fffffff) return CHUNK_ATTN_UNSUPPORTED;
-  e = launch_fwd(p, desc->head_dim, L.nq, (int)blocks, stream);
+  ProfileEvents pe = profile_events();
+  profile_events() = ProfileEvents{};
+  if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return hip_fail(e, "event record");
+  e = launch_fwd(p, desc->head_dim, (int)blocks, stream);
   if (e != hipSuccess) return hip_fail(e, "forward launch");
+  if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return hip_fail(e, "event record");
   return CHUNK_ATTN_OK;
 }
 

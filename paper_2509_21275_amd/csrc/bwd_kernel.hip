@@ -414,9 +414,14 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const std::v
     }
     const int64_t blocks = (int64_t)items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    ProfileEvents pe = profile_events();
+    profile_events() = ProfileEvents{};
+    hipError_t e;
+    if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((bwd_main_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return e;
   }
   {
     const int64_t n8 = n_pairs * (D / 8);

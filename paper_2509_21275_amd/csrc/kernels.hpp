@@ -13,7 +13,9 @@ struct FwdParams {
   const __bf16* v;
   __bf16* o;
   float* lse;
+  const __bf16* vt;         // transposed V images [Hkv][total_kv_tiles][D][64]
   const FwdItem* items;
+  int64_t total_kv_tiles;
   int32_t num_q_heads, num_kv_heads, group;  // group = Hq / Hkv
   int32_t heads_per_wg;                      // query heads of one group handled by one workgroup (1, 2 or 4)
   int32_t head_splits;                       // group / heads_per_wg
@@ -23,7 +25,13 @@ struct FwdParams {
 
 // rows of query tile per forward work item for a given head layout
 inline int fwd_heads_per_wg(int group) { return group % 4 == 0 ? 4 : (group % 2 == 0 ? 2 : 1); }
-inline int fwd_tile_rows(int group, int nq) { return 32 * nq * (4 / fwd_heads_per_wg(group)); }
+inline int fwd_tile_rows(int group) { return 32 * (4 / fwd_heads_per_wg(group)); }
+
+// Events armed by chunk_attn_profile_events for the calling thread (null when disarmed).
+struct ProfileEvents {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+ProfileEvents& profile_events();
 
 struct BwdParams {
   const __bf16* q;
@@ -57,7 +65,10 @@ void bwd_prepare(const chunk_attn_desc* d, std::vector<BwdItem>& items, size_t* 
 hipError_t launch_bwd(const chunk_attn_desc* d, const BwdArgs& a, const std::vector<BwdItem>& items,
                       hipStream_t stream);
 
-size_t fwd_smem_bytes(int head_dim);
-hipError_t launch_fwd(const FwdParams& p, int head_dim, int nq, int num_blocks, hipStream_t stream);
+hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, hipStream_t stream);
+
+// Transposed 64-row tile images of x[rows][num_heads][head_dim]: out[num_heads][total_tiles][head_dim][64].
+hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, const TileJob* jobs, int num_jobs,
+                            int64_t total_tiles, __bf16* out, hipStream_t stream);
 
 }  // namespace chunk_attn

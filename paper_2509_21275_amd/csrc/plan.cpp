@@ -36,19 +36,47 @@ int64_t pair_count(const chunk_attn_desc* d) {
   return n;
 }
 
+int64_t count_tiles(const chunk_attn_desc* d, bool kv) {
+  int64_t n = 0;
+  for (int t = 0; t < d->num_segments; ++t) n += ((kv ? d->segments[t].kv_len : d->segments[t].q_len) + 63) / 64;
+  return n;
+}
+
+std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, std::vector<int32_t>* seg_tile0) {
+  std::vector<TileJob> jobs;
+  if (seg_tile0) seg_tile0->clear();
+  for (int t = 0; t < d->num_segments; ++t) {
+    const chunk_attn_seg& s = d->segments[t];
+    const int32_t start = kv ? s.kv_start : s.q_start, len = kv ? s.kv_len : s.q_len;
+    if (seg_tile0) seg_tile0->push_back((int32_t)jobs.size());
+    for (int32_t r = 0; r < len; r += 64) {
+      TileJob j;
+      j.src_row0 = start + r;
+      j.valid_rows = std::min<int32_t>(64, len - r);
+      j.image = (int32_t)jobs.size();
+      j.pad = 0;
+      jobs.push_back(j);
+    }
+  }
+  return jobs;
+}
+
 std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows) {
   std::vector<FwdItem> items;
+  int32_t kv_tile0 = 0;
   for (int t = 0; t < d->num_segments; ++t) {
     const chunk_attn_seg& s = d->segments[t];
     const int32_t C = s.kv_len - s.q_len;
     for (int32_t i0 = 0; i0 < s.q_len; i0 += tile_rows) {
-      FwdItem it;
+      FwdItem it{};
+      it.kv_tile0 = kv_tile0;
       it.q_row0 = s.q_start + i0;
       it.q_rows = std::min<int32_t>(tile_rows, s.q_len - i0);
       it.kv_row0 = s.kv_start;
       it.n0 = C + i0 + 1;
       items.push_back(it);
     }
+    kv_tile0 += (s.kv_len + 63) / 64;
   }
   // most keys first, so the long items start early and the short ones fill the tail
   std::stable_sort(items.begin(), items.end(), [](const FwdItem& a, const FwdItem& b) {

@@ -13,12 +13,21 @@
 
 namespace chunk_attn {
 
+// A 64-row tile of a tensor to be transposed by the pre-pass: rows [src_row0, src_row0 + valid_rows).
+struct TileJob {
+  int32_t src_row0, valid_rows;
+  int32_t image;  // index of the output image (per head)
+  int32_t pad;
+};
+
 // Forward work item: a tile of consecutive query rows of one segment.
 struct FwdItem {
-  int32_t q_row0;   // first query row (global)
-  int32_t q_rows;   // valid rows in the tile (>= 1)
-  int32_t kv_row0;  // first key row of the segment (global)
-  int32_t n0;       // keys visible to the tile's first row: C + i0 + 1; row r sees n0 + r
+  int32_t q_row0;    // first query row (global)
+  int32_t q_rows;    // valid rows in the tile (>= 1)
+  int32_t kv_row0;   // first key row of the segment (global)
+  int32_t n0;        // keys visible to the tile's first row: C + i0 + 1; row r sees n0 + r
+  int32_t kv_tile0;  // index of the transposed image of the segment's first 64-key tile
+  int32_t pad0, pad1, pad2;
 };
 
 // Backward work item: a tile of consecutive key rows of one segment and the queries that see it.
@@ -39,6 +48,10 @@ int64_t pair_count(const chunk_attn_desc* d);
 std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows);
 // Tiles of `tile_rows` key rows per segment, most work first.
 std::vector<BwdItem> plan_bwd(const chunk_attn_desc* d, int tile_rows);
+// 64-row tiles of every segment's key range (kv = true) or query range (kv = false), in segment order;
+// seg_tile0[t] receives the image index of segment t's first tile.
+std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, std::vector<int32_t>* seg_tile0);
+int64_t count_tiles(const chunk_attn_desc* d, bool kv);
 // Key-row ranges [begin, end) not covered by any segment (to be zero-filled when not accumulating).
 std::vector<std::pair<int32_t, int32_t>> uncovered_kv_ranges(const chunk_attn_desc* d);
 

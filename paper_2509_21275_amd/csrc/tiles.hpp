@@ -1,0 +1,87 @@
+// LDS tile layouts, global->LDS DMA and MFMA operand reads shared by the attention kernels (gfx950).
+//
+// Every MFMA operand is fetched with one 16-byte LDS read per lane (8 bf16 along the contraction index).
+// Tiles are stored as rows of 16-byte chunks; the chunk position inside a row is permuted per row
+// ("swizzle") so that the 16 lanes served together by a ds_read_b128 -- 16 consecutive rows, same logical
+// chunk -- fall on 16 distinct bank groups.  Tiles are filled by global_load_lds (the data never passes
+// through registers): lane x of a wave-wide load writes LDS bytes [16 x, 16 x + 16) past a wave-uniform
+// base, so each lane simply fetches the global chunk that belongs at its LDS position.
+#pragma once
+#include "device_common.hpp"
+
+namespace chunk_attn {
+
+// physical chunk position of logical chunk c in row `row` of a tile with CHUNKS 16-byte chunks per row
+template <int CHUNKS>
+__device__ __forceinline__ int swz(int row, int c) {
+  if constexpr (CHUNKS == 16) {
+    // 256-byte rows: rotate by a 4x4 bit-transposed row index; conflict-free for 16 consecutive rows
+    const int f = ((row & 3) << 2) | ((row >> 2) & 3);
+    return (c + f) & 15;
+  } else {
+    static_assert(CHUNKS == 8, "tiles have 8 or 16 chunks per row");
+    // 128-byte rows: two rows share a 256-byte bank line, so the permutation changes every other row
+    return c ^ ((row >> 1) & 7);
+  }
+}
+// logical chunk stored at physical position pc (inverse of swz)
+template <int CHUNKS>
+__device__ __forceinline__ int unswz(int row, int pc) {
+  if constexpr (CHUNKS == 16) {
+    const int f = ((row & 3) << 2) | ((row >> 2) & 3);
+    return (pc - f) & 15;
+  } else {
+    return pc ^ ((row >> 1) & 7);
+  }
+}
+// element offset of (row, logical chunk c) in a swizzled tile
+template <int CHUNKS>
+__device__ __forceinline__ int tile_elem(int row, int c) {
+  return (row * CHUNKS + swz<CHUNKS>(row, c)) * 8;
+}
+
+__device__ __forceinline__ void dma16(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// DMA a row-major tile of ROWS x (8 CHUNKS) bf16 from global rows `src + min(r, last_row) * row_stride`
+// into a swizzled LDS tile.  Called by all 256 threads of the workgroup.
+template <int ROWS, int CHUNKS>
+__device__ __forceinline__ void dma_rows_tile(const __bf16* src, int64_t row_stride, int last_row, __bf16* lds_tile,
+                                              int wave, int lane) {
+  constexpr int N = ROWS * CHUNKS / 256;  // instructions per thread
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const int x0 = (i * 4 + wave) * 64;   // wave-uniform first chunk of this instruction
+    const int x = x0 + lane;
+    const int row = x / CHUNKS, pc = x % CHUNKS;
+    const int c = unswz<CHUNKS>(row, pc);
+    dma16(src + (int64_t)min(row, last_row) * row_stride + c * 8, lds_tile + x0 * 8);
+  }
+}
+
+// DMA a contiguous image of BYTES bytes (already in LDS order) into LDS.
+template <int BYTES>
+__device__ __forceinline__ void dma_image(const __bf16* src, __bf16* lds_tile, int wave, int lane) {
+  constexpr int N = BYTES / 16 / 256;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const int x0 = (i * 4 + wave) * 64;
+    dma16(src + (int64_t)(x0 + lane) * 8, lds_tile + x0 * 8);
+  }
+}
+
+// 8 bf16 of (row, logical chunk c)
+template <int CHUNKS>
+__device__ __forceinline__ bf16x8 lds_chunk(const __bf16* tile, int row, int c) {
+  return *reinterpret_cast<const bf16x8*>(tile + tile_elem<CHUNKS>(row, c));
+}
+
+// Position p (0..63) of a 64-wide transposed tile row holds contraction index cperm(p): the order in which
+// an accumulator tile presents its rows when it is reused as a B operand (device_common.hpp, "C-order").
+__host__ __device__ __forceinline__ int cperm(int p) {
+  return (p & ~15) | ((p & 4) << 1) | ((p & 8) >> 1) | (p & 3);
+}
+
+}  // namespace chunk_attn

@@ -1,0 +1,59 @@
+// Pre-pass that prepares transposed operand tiles.
+//
+// For X[rows][H][D] (bf16) and a list of 64-row tiles, writes for every (head, tile) an "image"
+// T[D][64] with T[c][p] = X[row0 + cperm(p)][head][c] (zero past the tile's valid rows), already in
+// the swizzled chunk order in which the attention kernels keep it in LDS.  The attention kernels then
+// fetch an image with a linear global->LDS copy and read MFMA operands whose contraction index runs
+// along X's row index (V^T for O += P V, K^T for dQ += dS K, Q^T and dO^T for dK, dV) with plain
+// 16-byte LDS reads.  Cost: one read and one write of X, negligible next to the attention itself.
+#include "kernels.hpp"
+#include "tiles.hpp"
+
+namespace chunk_attn {
+
+template <int D>
+__global__ __launch_bounds__(256) void transpose_tiles_kernel(const __bf16* __restrict__ x, int num_heads,
+                                                              const TileJob* __restrict__ jobs, int64_t total_tiles,
+                                                              __bf16* __restrict__ out) {
+  constexpr int P = D + 2;  // LDS pitch (elements) of the staging tile
+  __shared__ __bf16 stage[64 * P];
+  const int tid = threadIdx.x;
+  const int h = blockIdx.x % num_heads;
+  const TileJob job = jobs[blockIdx.x / num_heads];
+  const int64_t stride = (int64_t)num_heads * D;
+  for (int idx = tid; idx < 64 * (D / 8); idx += 256) {
+    const int row = idx / (D / 8), c = idx % (D / 8);
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (__bf16)0.0f;
+    if (row < job.valid_rows) v = *reinterpret_cast<const bf16x8*>(x + ((int64_t)job.src_row0 + row) * stride + (int64_t)h * D + c * 8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) stage[row * P + c * 8 + i] = v[i];
+  }
+  __syncthreads();
+  __bf16* img = out + ((int64_t)h * total_tiles + job.image) * (D * 64);
+  for (int idx = tid; idx < D * 8; idx += 256) {
+    const int d = idx / 8, pc = idx % 8;
+    const int c = unswz<8>(d, pc);
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = stage[cperm(8 * c + i) * P + d];
+    *reinterpret_cast<bf16x8*>(img + (int64_t)idx * 8) = v;
+  }
+}
+
+hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, const TileJob* jobs, int num_jobs,
+                            int64_t total_tiles, __bf16* out, hipStream_t stream) {
+  if (num_jobs == 0) return hipSuccess;
+  const int64_t blocks = (int64_t)num_jobs * num_heads;
+  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+  if (head_dim == 128)
+    hipLaunchKernelGGL((transpose_tiles_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, stream, x, num_heads, jobs,
+                       total_tiles, out);
+  else
+    hipLaunchKernelGGL((transpose_tiles_kernel<64>), dim3((unsigned)blocks), dim3(256), 0, stream, x, num_heads, jobs,
+                       total_tiles, out);
+  return hipGetLastError();
+}
+
+}  // namespace chunk_attn
