@@ -79,12 +79,12 @@ void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_plan) {
   size_t n_items = 0;
   if (with_plan) {
     L.items = plan_fwd(d, L.tile_rows);
-    L.jobs = tile_jobs(d, true, nullptr);
+    L.jobs = tile_jobs(d, true, 64, nullptr);
     n_items = L.items.size();
   } else {
     for (int t = 0; t < d->num_segments; ++t) n_items += (d->segments[t].q_len + L.tile_rows - 1) / L.tile_rows;
   }
-  L.kv_tiles = count_tiles(d, true);
+  L.kv_tiles = count_tiles(d, true, 64);
   L.items_bytes = n_items * sizeof(FwdItem);
   L.jobs_off = align_up(L.items_bytes);
   L.blob_bytes = L.jobs_off + (size_t)L.kv_tiles * sizeof(TileJob);
@@ -141,7 +141,11 @@ int chunk_attn_workspace_bytes(const chunk_attn_desc* desc, size_t* fwd_bytes, s
     layout_fwd(desc, L, false);
     *fwd_bytes = L.total;
   }
-  if (bwd_bytes) *bwd_bytes = bwd_workspace_bytes(desc);
+  if (bwd_bytes) {
+    BwdPlan P;
+    bwd_layout(desc, P, false);
+    *bwd_bytes = P.total;
+  }
   return CHUNK_ATTN_OK;
 }
 
@@ -163,7 +167,7 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   hipError_t e = g_ring.upload(ws, blob.data(), blob.size(), stream);
   if (e != hipSuccess) return hip_fail(e, "schedule upload");
   __bf16* vt = reinterpret_cast<__bf16*>(ws + L.vt_off);
-  e = launch_transpose(static_cast<const __bf16*>(v), desc->num_kv_heads, desc->head_dim,
+  e = launch_transpose(static_cast<const __bf16*>(v), desc->num_kv_heads, desc->head_dim, 64,
                        reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.jobs.size(), L.kv_tiles, vt, stream);
   if (e != hipSuccess) return hip_fail(e, "transpose launch");
 
@@ -201,7 +205,9 @@ int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   if (rc != CHUNK_ATTN_OK) return rc;
   if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return CHUNK_ATTN_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return CHUNK_ATTN_INVALID_ARG;
-  if (workspace_bytes < bwd_workspace_bytes(desc)) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
+  BwdPlan P;
+  bwd_layout(desc, P, true);
+  if (workspace_bytes < P.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   BwdArgs a;
   a.q = static_cast<const __bf16*>(q);
@@ -215,12 +221,10 @@ int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   a.dv = static_cast<__bf16*>(dv);
   a.accumulate = accumulate_dkv != 0;
   a.workspace = static_cast<char*>(workspace);
-  std::vector<BwdItem> items;
-  size_t items_off = 0;
-  bwd_prepare(desc, items, &items_off);
-  hipError_t e = g_ring.upload(a.workspace + items_off, items.data(), items.size() * sizeof(BwdItem), stream);
+  const std::vector<char> blob = bwd_blob(P);
+  hipError_t e = g_ring.upload(a.workspace, blob.data(), blob.size(), stream);
   if (e != hipSuccess) return hip_fail(e, "schedule upload");
-  e = launch_bwd(desc, a, items, stream);
+  e = launch_bwd(desc, a, P, stream);
   if (e != hipSuccess) return hip_fail(e, "backward launch");
   return CHUNK_ATTN_OK;
 }

@@ -1,95 +1,63 @@
 // Chunk attention backward for gfx950 (gradients of L = sum(O .* dO) under the chunk mask of the
 // paper's section 3.1; key/value gradients include the context rows, section 2.1 / 3.2.2).
 //
-// Three kernels:
-//   bwd_pre   D_i = <dO_i, O_i> per (head, row), and zero the float32 dQ accumulator;
-//   bwd_main  one workgroup per tile of 128 key rows of one key/value head.  It keeps that K/V tile
-//             resident (K in LDS and registers, V in registers) and walks over the query heads of the
-//             group and over the 64-row query tiles that see the key tile, recomputing
-//             P = exp(S - LSE) from the saved log-sum-exp.  dK and dV accumulate in registers over
-//             all queries and all heads of the group; dQ contributions are added with float32
-//             atomics into the workspace;
-//   bwd_post  dQ = bf16(scale * accumulator); zero the key rows no segment covers.
+// Two reductions are needed -- dQ sums over keys, dK/dV sum over queries -- and a workgroup can keep
+// only one of them in registers.  Float atomics for the other one are far too slow on this chip at the
+// rate an attention backward produces them, so each reduction gets its own kernel and every output
+// element is written exactly once (the result is also bit-reproducible):
 //
-// Orientation: S = Q K^T is computed with the key index along lanes, so P and dS come out of the MFMA
-// already in B-operand form for dV^T += dO^T P and dK^T += Q^T dS ("C-order", device_common.hpp);
-// only dS has to cross lanes (through LDS) for dQ += dS K.
-#include "kernels.hpp"
+//   bwd_pre   D_i = <dO_i, O_i> and LSE_i log2(e) per (head, row), stored in arrays padded to 64-row
+//             tiles per segment (+inf / 0 in the padding, so padded rows yield P = 0);
+//   transposes (transpose_kernel.hip) of K (32-row tiles) and of Q, dO (64-row tiles);
+//   bwd_dq    query-stationary, like the forward: S^T = K Q^T and dP^T = V dO^T per 32-key tile,
+//             dS^T = P^T (dP^T - D), dQ^T += K^T dS^T with dS^T fed back from the accumulator registers;
+//   bwd_dkv   key-stationary: one workgroup per 128 keys of one key/value head, K and V fragments in
+//             registers, walking the query heads of the group and the 64-row query tiles that see
+//             those keys: S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS with P and dS fed back
+//             from the accumulator registers.
+// P is recomputed from the saved log-sum-exp in both kernels.  All operands reach LDS by global->LDS
+// copies and are read with 16-byte LDS reads from swizzled tiles (tiles.hpp).
+#include <cstring>
+#include <type_traits>
 
-#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
+#include "kernels.hpp"
+#include "tiles.hpp"
 
 namespace chunk_attn {
 
 namespace {
 
-constexpr int BN = 128;  // key rows per workgroup
-constexpr int BM = 64;   // query rows per iteration
-constexpr int DSP = 96;  // pitch (elements) of the dS^T tile [BN][BM]
+constexpr float kLog2e = 1.4426950408889634f;
 
-// Element offset inside a row-major bf16 LDS tile with D columns.  D = 128: 256-byte rows whose sixteen
-// 16-byte groups are rotated by a per-row amount chosen so that both 16 consecutive rows at one column
-// group (row reads of 16 bytes) and 4 consecutive rows x 4 consecutive groups (transpose reads) fall on
-// distinct groups.  D = 64: padded rows.
-template <int D>
-__device__ __forceinline__ int tile_off(int row, int col) {
-  if constexpr (D == 128) {
-    const int f = ((row & 3) << 2) | ((row >> 2) & 3);
-    return row * 128 + ((((col >> 3) + f) & 15) << 3) + (col & 7);
-  } else {
-    return row * (D + 8) + col;
-  }
-}
-template <int D>
-constexpr int tile_elems(int rows) { return D == 128 ? rows * 128 : rows * (D + 8); }
-
-// A operand in C-order gathered from a tile T[k][m] laid out with tile_off<D>.
-template <int D>
-__device__ __forceinline__ bf16x8 a_tr(const __bf16* tile, int k0, int m0, int lane) {
-  const int row = k0 + 4 * (lane >> 5) + ((lane & 15) >> 2);
-  const int col = m0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  s16x4 lo = lds_read_tr(tile + tile_off<D>(row, col));
-  s16x4 hi = lds_read_tr(tile + tile_off<D>(row + 8, col));
-  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
+// ------------------------------------------------------------------------------------------------
+// bwd_pre: one workgroup per (64-row query tile, head); 4 threads per row.
+// ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void bwd_pre_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o,
-                                                      float* __restrict__ dsum, float* __restrict__ dq_acc,
-                                                      int total_q, int num_q_heads) {
-  constexpr int LPR = D / 8;  // lanes per (row, head)
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t pair = gid / LPR;  // row * Hq + head
-  const int part = (int)(gid % LPR);
-  const int64_t n_pairs = (int64_t)total_q * num_q_heads;
+                                                      const float* __restrict__ lse, const TileJob* __restrict__ jobs,
+                                                      int64_t total_q_tiles, int total_q, int num_q_heads,
+                                                      float* __restrict__ lse2p, float* __restrict__ dsp) {
+  const int head = blockIdx.x % num_q_heads;
+  const TileJob job = jobs[blockIdx.x / num_q_heads];
+  const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
   float acc = 0.f;
-  if (pair < n_pairs) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + pair * D + part * 8);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(d_o + pair * D + part * 8);
+  const bool valid = r < job.valid_rows;
+  if (valid) {
+    const int64_t base = ((int64_t)(job.src_row0 + r) * num_q_heads + head) * D + part * (D / 4);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
-    f32x4 z = {0.f, 0.f, 0.f, 0.f};
-    *reinterpret_cast<f32x4*>(dq_acc + pair * D + part * 8) = z;
-    *reinterpret_cast<f32x4*>(dq_acc + pair * D + part * 8 + 4) = z;
-  }
+    for (int c = 0; c < D / 32; ++c) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + base + c * 8);
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(d_o + base + c * 8);
 #pragma unroll
-  for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
-  if (pair < n_pairs && part == 0) {
-    const int64_t row = pair / num_q_heads, head = pair % num_q_heads;
-    dsum[head * total_q + row] = acc;
+      for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
+    }
   }
-}
-
-template <int D>
-__global__ __launch_bounds__(256) void bwd_post_kernel(const float* __restrict__ dq_acc, __bf16* __restrict__ dq,
-                                                       int64_t n_elems8, float scale) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n_elems8) {
-    const f32x4 a = *reinterpret_cast<const f32x4*>(dq_acc + i * 8);
-    const f32x4 b = *reinterpret_cast<const f32x4*>(dq_acc + i * 8 + 4);
-    *reinterpret_cast<bf16x8*>(dq + i * 8) =
-        pack8(a[0] * scale, a[1] * scale, a[2] * scale, a[3] * scale, b[0] * scale, b[1] * scale, b[2] * scale,
-              b[3] * scale);
+  acc += __shfl_xor(acc, 1);
+  acc += __shfl_xor(acc, 2);
+  if (part == 0) {
+    const int64_t slot = ((int64_t)head * total_q_tiles + job.image) * 64 + r;
+    dsp[slot] = valid ? acc : 0.f;
+    lse2p[slot] = valid ? lse[(int64_t)head * total_q + job.src_row0 + r] * kLog2e : INFINITY;
   }
 }
 
@@ -99,139 +67,324 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(u32x4* __restrict__ p, i
   if (i < n16) p[i] = u32x4{0u, 0u, 0u, 0u};
 }
 
+// ------------------------------------------------------------------------------------------------
+// bwd_dq
+// ------------------------------------------------------------------------------------------------
+struct DqParams {
+  const __bf16 *q, *k, *v, *d_o;
+  const __bf16* kt;      // transposed K images [Hkv][total_kv32_tiles][D][32]
+  const float* lse2p;    // [Hq][total_q_tiles * 64]
+  const float* dsp;
+  __bf16* dq;
+  const DqItem* items;
+  int64_t total_kv32_tiles, total_q_tiles;
+  int32_t num_q_heads, num_kv_heads, group, heads_per_wg, head_splits;
+  float scale, scale_log2;
+};
+
 template <int D>
-__global__ __launch_bounds__(256) void bwd_main_kernel(BwdParams p) {
-  constexpr int DK = D / 16;  // k-steps over the head dimension
-  constexpr int DB = D / 32;  // 32-row blocks along the head dimension
-  constexpr int QCH = BM * D / 8 / 256;  // 16-byte chunks per thread per Q (or dO) tile
-  constexpr int KCH = BN * D / 8 / 256;
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
+  constexpr int BN = 32;       // key rows per LDS tile
+  constexpr int KC = D / 8;    // 16-byte chunks per K / V row
+  constexpr int DK = D / 16;   // k-steps over the head dimension
+  constexpr int DB = D / 32;   // 32-row blocks of dQ^T
+  constexpr int KT = BN * D;   // elements per tile
 
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  __bf16* Kt = reinterpret_cast<__bf16*>(smem);          // [BN][D]
-  __bf16* Qt = Kt + tile_elems<D>(BN);                    // [2][BM][D]
-  __bf16* Gt = Qt + 2 * tile_elems<D>(BM);                // [2][BM][D]   (dO)
-  __bf16* dSt = Gt + 2 * tile_elems<D>(BM);               // [BN][DSP]    (dS^T)
-  float* lse_s = reinterpret_cast<float*>(dSt + BN * DSP);  // [2][BM]
-  float* dsum_s = lse_s + 2 * BM;                           // [2][BM]
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __bf16* Ks = reinterpret_cast<__bf16*>(smem);  // [2][BN][D]
+  __bf16* Vs = Ks + 2 * KT;                      // [2][BN][D]
+  __bf16* Ts = Vs + 2 * KT;                      // [2][D][BN]  K^T image
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  const int inner_n = p.num_kv_heads * p.head_splits;
+  const int inner = blockIdx.x % inner_n;
+  const DqItem it = p.items[blockIdx.x / inner_n];
+  const int kvh = inner % p.num_kv_heads, hs = inner / p.num_kv_heads;
+  const int head = kvh * p.group + hs * p.heads_per_wg + wave % p.heads_per_wg;
+  const int wave_row0 = (wave / p.heads_per_wg) * 32;
+
+  const int n_wg = it.n0 + it.q_rows - 1;
+  const int nt_wg = (n_wg + BN - 1) / BN;
+  int nt_w = 0;
+  if (wave_row0 < it.q_rows) {
+    const int last = min(wave_row0 + 32, it.q_rows) - 1;
+    nt_w = (it.n0 + last + BN - 1) / BN;
+  }
+
+  const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
+  const __bf16* __restrict__ Kg = p.k + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
+  const __bf16* __restrict__ Vg = p.v + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
+  const __bf16* __restrict__ Timg = p.kt + ((int64_t)kvh * p.total_kv32_tiles + it.kv_tile0) * KT;
+
+  constexpr int NK = BN * KC / 256, NT = KT / 8 / 256;
+  unsigned k_src[NK];
+  int k_row[NK];
+#pragma unroll
+  for (int i = 0; i < NK; ++i) {
+    const int x = (i * 4 + wave) * 64 + lane;
+    k_row[i] = x / KC;
+    k_src[i] = (unsigned)(k_row[i] * (int)kv_stride + unswz<KC>(k_row[i], x % KC) * 8);
+  }
+  auto dma_tile = [&](int t, int buf) {
+    const int64_t toff = (int64_t)(BN * t) * kv_stride;  // wave-uniform
+    const int last_row = n_wg - 1 - BN * t;
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+      unsigned off = k_src[i];
+      if (last_row < BN - 1) off -= (unsigned)((k_row[i] - min(k_row[i], last_row)) * (int)kv_stride);
+      dma16(Kg + toff + off, Ks + buf * KT + (i * 4 + wave) * 512);
+      dma16(Vg + toff + off, Vs + buf * KT + (i * 4 + wave) * 512);
+    }
+    const __bf16* tsrc = Timg + (int64_t)t * KT;
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+      dma16(tsrc + (unsigned)(((i * 4 + wave) * 64 + lane) * 8), Ts + buf * KT + (i * 4 + wave) * 512);
+  };
+
+  dma_tile(0, 0);
+
+  // Q and dO fragments (B operands): lane holds X[row = l32][16 ks + 8 hh ..+7]
+  bf16x8 qf[DK], gf[DK];
+  const int r_own = min(wave_row0 + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
+  {
+    const int64_t off = (int64_t)(it.q_row0 + r_own) * q_stride + (int64_t)head * D + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
+      gf[ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
+    }
+  }
+  const int64_t slot = (int64_t)head * p.total_q_tiles * 64 + it.q_slot0 + r_own;
+  const float lse2 = p.lse2p[slot], dsum = p.dsp[slot];
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 dq[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) dq[db] = zero16;
+  const float c = p.scale_log2;
+
+  int k_off[DK], t_off[2];
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) k_off[ks] = tile_elem<KC>(l32, 2 * ks + hh);
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) t_off[ks] = tile_elem<4>(l32, 2 * ks + hh);
+
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  auto tile_step = [&](int t, auto buf_c) {
+    constexpr int buf = decltype(buf_c)::value;
+    if (t + 1 < nt_wg) dma_tile(t + 1, buf ^ 1);
+
+    if (t < nt_w) {
+      const __bf16* Kt = Ks + buf * KT;
+      const __bf16* Vt = Vs + buf * KT;
+      const __bf16* Tt = Ts + buf * KT;
+      // ---- S^T = K Q^T, dP^T = V dO^T : [32 keys] x [32 queries] ----
+      f32x16 s, dp;
+#pragma unroll
+      for (int ks = 0; ks < DK; ++ks) {
+        const bf16x8 ak = *reinterpret_cast<const bf16x8*>(Kt + k_off[ks]);
+        const bf16x8 av = *reinterpret_cast<const bf16x8*>(Vt + k_off[ks]);
+        s = mfma32(ak, qf[ks], ks == 0 ? zero16 : s);
+        dp = mfma32(av, gf[ks], ks == 0 ? zero16 : dp);
+      }
+      // ---- P = exp2(S c - LSE), dS = P (dP - D); masked keys give P = 0 ----
+      float pe[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) pe[i] = __builtin_amdgcn_exp2f(s[i] * c - lse2);
+      if (BN * t + BN > it.n0 + wave_row0) {
+        const int lim = it.n0 + wave_row0 + l32 - BN * t;  // visible iff local key index < lim
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = 8 * (i >> 2) + 4 * hh + (i & 3);
+          if (j >= lim) pe[i] = 0.f;
+        }
+      }
+      float ds[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) ds[i] = pe[i] * (dp[i] - dsum);
+      const bf16x8 f0 = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+      const bf16x8 f1 = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+      // ---- dQ^T += K^T dS^T : [D] x [32 queries], contraction over the 32 keys ----
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Tt + t_off[0] + db * 32 * BN);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Tt + t_off[1] + db * 32 * BN);
+        dq[db] = mfma32(a0, f0, dq[db]);
+        dq[db] = mfma32(a1, f1, dq[db]);
+      }
+    }
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  };
+
+  for (int t = 0; t < nt_wg; t += 2) {
+    tile_step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < nt_wg) tile_step(t + 1, std::integral_constant<int, 1>{});
+  }
+
+  // ---- epilogue: dQ = scale * dQ^T ----
+  {
+    const int r = wave_row0 + l32;
+    if (r < it.q_rows) {
+      __bf16* op = p.dq + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const bf16x4 v = pack4(dq[db][4 * g] * p.scale, dq[db][4 * g + 1] * p.scale, dq[db][4 * g + 2] * p.scale,
+                                 dq[db][4 * g + 3] * p.scale);
+          *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * g + 4 * hh) = v;
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bwd_dkv
+// ------------------------------------------------------------------------------------------------
+struct DkvParams {
+  const __bf16 *q, *k, *v, *d_o;
+  const __bf16* qt;     // transposed Q images  [Hq][total_q_tiles][D][64]
+  const __bf16* gt;     // transposed dO images [Hq][total_q_tiles][D][64]
+  const float* lse2p;   // [Hq][total_q_tiles * 64]
+  const float* dsp;
+  __bf16 *dk, *dv;
+  const DkvItem* items;
+  int64_t total_q_tiles;
+  int32_t num_q_heads, num_kv_heads, group;
+  float scale, scale_log2;
+  int32_t accumulate;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_dkv_kernel(DkvParams p) {
+  constexpr int BM = 64;       // query rows per LDS tile
+  constexpr int KC = D / 8;
+  constexpr int DK = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int QT = BM * D;   // elements per tile / image
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __bf16* Qs = reinterpret_cast<__bf16*>(smem);  // [2][BM][D]  rows
+  __bf16* Gs = Qs + 2 * QT;                      // [2][BM][D]  rows (dO)
+  __bf16* QTs = Gs + 2 * QT;                     // [2][D][BM]  image
+  __bf16* GTs = QTs + 2 * QT;                    // [2][D][BM]  image
+  float* lse_s = reinterpret_cast<float*>(GTs + 2 * QT);  // [2][BM]
+  float* dsum_s = lse_s + 2 * BM;                          // [2][BM]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
 
   const int kvh = blockIdx.x % p.num_kv_heads;
-  const BwdItem it = p.items[blockIdx.x / p.num_kv_heads];
+  const DkvItem it = p.items[blockIdx.x / p.num_kv_heads];
   const int G = p.group;
   const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
   const float c = p.scale_log2;
 
-  // ---- resident K tile (LDS) and this wave's K / V fragments (registers) ----
-  {
-    const __bf16* Kg = p.k + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
-#pragma unroll
-    for (int ci = 0; ci < KCH; ++ci) {
-      const int idx = tid + 256 * ci;
-      const int row = idx / (D / 8), col = (idx % (D / 8)) * 8;
-      const int64_t grow = min(row, it.kv_rows - 1);
-      *reinterpret_cast<u32x4*>(Kt + tile_off<D>(row, col)) = *reinterpret_cast<const u32x4*>(Kg + grow * kv_stride + col);
-    }
-  }
-  bf16x8 kf[DK], vf[DK];  // B operands: lane holds K[key = 32 wave + l32][16 ks + 8 hh ..+7]
+  // this wave's K / V fragments (B operands): lane holds X[key = 32 wave + l32][16 ks + 8 hh ..+7]
+  bf16x8 kf[DK], vf[DK];
   {
     const int64_t grow = it.kv_row0 + min(32 * wave + l32, it.kv_rows - 1);
-    const __bf16* kp = p.k + grow * kv_stride + (int64_t)kvh * D + 8 * hh;
-    const __bf16* vp = p.v + grow * kv_stride + (int64_t)kvh * D + 8 * hh;
+    const int64_t off = grow * kv_stride + (int64_t)kvh * D + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < DK; ++ks) {
-      kf[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(vp + 16 * ks);
+      kf[ks] = *reinterpret_cast<const bf16x8*>(p.k + off + 16 * ks);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(p.v + off + 16 * ks);
     }
   }
 
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 dkacc[DB], dvacc[DB];  // dK^T, dV^T: [D] x [32 keys of this wave]
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { dkacc[db][i] = 0.f; dvacc[db][i] = 0.f; }
+  for (int db = 0; db < DB; ++db) { dkacc[db] = zero16; dvacc[db] = zero16; }
 
-  const int nqt = (it.q_rows + BM - 1) / BM;
+  const int nqt = it.n_qt - it.qt_first;
   const int n_iter = nqt * G;
 
-  // ---- Q / dO tile staging ----
-  u32x4 qreg[QCH], greg[QCH];
-  float lse_reg = 0.f, dsum_reg = 0.f;
-  auto load_tiles = [&](int iter) {
-    const int hg = iter / nqt, qt = iter % nqt;
+  // ---- staging of one (head, query tile): Q, dO rows; Q^T, dO^T images; LSE, D ----
+  constexpr int NQ = BM * KC / 256, NI = QT / 8 / 256;
+  unsigned q_src[NQ];
+  int q_row[NQ];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const int x = (i * 4 + wave) * 64 + lane;
+    q_row[i] = x / KC;
+    q_src[i] = (unsigned)(q_row[i] * (int)q_stride + unswz<KC>(q_row[i], x % KC) * 8);
+  }
+  auto dma_stage = [&](int iter, int buf) {
+    const int hg = iter / nqt, qt = it.qt_first + iter % nqt;
     const int head = kvh * G + hg;
-    const int rows_left = it.q_rows - qt * BM;  // >= 1
-    const int64_t base_row = (int64_t)it.q_row0 + qt * BM;
+    const int last_row = it.q_len - 1 - qt * BM;  // >= 0
+    const int64_t roff = (int64_t)(it.q_row_seg + qt * BM) * q_stride + (int64_t)head * D;  // wave-uniform
 #pragma unroll
-    for (int ci = 0; ci < QCH; ++ci) {
-      const int idx = tid + 256 * ci;
-      const int row = idx / (D / 8), col = (idx % (D / 8)) * 8;
-      const int64_t grow = base_row + min(row, rows_left - 1);
-      qreg[ci] = *reinterpret_cast<const u32x4*>(p.q + grow * q_stride + (int64_t)head * D + col);
-      greg[ci] = *reinterpret_cast<const u32x4*>(p.d_o + grow * q_stride + (int64_t)head * D + col);
+    for (int i = 0; i < NQ; ++i) {
+      unsigned off = q_src[i];
+      if (last_row < BM - 1) off -= (unsigned)((q_row[i] - min(q_row[i], last_row)) * (int)q_stride);
+      dma16(p.q + roff + off, Qs + buf * QT + (i * 4 + wave) * 512);
+      dma16(p.d_o + roff + off, Gs + buf * QT + (i * 4 + wave) * 512);
     }
-    if (tid < BM) {
-      if (tid < rows_left) {
-        lse_reg = p.lse[(int64_t)head * p.total_q + base_row + tid] * 1.4426950408889634f;
-        dsum_reg = p.dsum[(int64_t)head * p.total_q + base_row + tid];
-      } else {
-        lse_reg = INFINITY;  // rows past the segment end: P = exp2(S - inf) = 0
-        dsum_reg = 0.f;
-      }
-    }
-  };
-  auto store_tiles = [&](int buf) {
+    const int64_t tile = (int64_t)head * p.total_q_tiles + it.q_tile0 + qt;  // wave-uniform
 #pragma unroll
-    for (int ci = 0; ci < QCH; ++ci) {
-      const int idx = tid + 256 * ci;
-      const int row = idx / (D / 8), col = (idx % (D / 8)) * 8;
-      *reinterpret_cast<u32x4*>(Qt + buf * tile_elems<D>(BM) + tile_off<D>(row, col)) = qreg[ci];
-      *reinterpret_cast<u32x4*>(Gt + buf * tile_elems<D>(BM) + tile_off<D>(row, col)) = greg[ci];
+    for (int i = 0; i < NI; ++i) {
+      const unsigned off = (unsigned)(((i * 4 + wave) * 64 + lane) * 8);
+      dma16(p.qt + tile * QT + off, QTs + buf * QT + (i * 4 + wave) * 512);
+      dma16(p.gt + tile * QT + off, GTs + buf * QT + (i * 4 + wave) * 512);
     }
-    if (tid < BM) {
-      lse_s[buf * BM + tid] = lse_reg;
-      dsum_s[buf * BM + tid] = dsum_reg;
-    }
+    if (wave == 0) dma4(p.lse2p + tile * 64 + lane, lse_s + buf * BM);
+    if (wave == 1) dma4(p.dsp + tile * 64 + lane, dsum_s + buf * BM);
   };
 
-  load_tiles(0);
-  store_tiles(0);
+  int q_off[DK], t_off[4];
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) q_off[ks] = tile_elem<KC>(l32, 2 * ks + hh);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) t_off[ks] = tile_elem<8>(l32, 2 * ks + hh);
+
+  // key index of this lane's column inside the segment, relative to the context: query i sees it iff i >= jrel
+  const int jrel = it.j0 + 32 * wave + l32 - it.ctx;
+
+  if (n_iter > 0) dma_stage(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  for (int iter = 0; iter < n_iter; ++iter) {
-    const int buf = iter & 1;
-    const int hg = iter / nqt, qt = iter % nqt;
-    if (iter + 1 < n_iter) load_tiles(iter + 1);
-
-    const __bf16* Qb = Qt + buf * tile_elems<D>(BM);
-    const __bf16* Gb = Gt + buf * tile_elems<D>(BM);
+  auto iter_step = [&](int iter, auto buf_c) {
+    constexpr int buf = decltype(buf_c)::value;
+    if (iter + 1 < n_iter) dma_stage(iter + 1, buf ^ 1);
+    const int qt = it.qt_first + iter % nqt;
+    const __bf16* Qb = Qs + buf * QT;
+    const __bf16* Gb = Gs + buf * QT;
+    const __bf16* QTb = QTs + buf * QT;
+    const __bf16* GTb = GTs + buf * QT;
 
     // ---- S = Q K^T and dP = dO V^T : [64 queries] x [32 keys of this wave] ----
-    f32x16 sacc[2], pacc[2];
+    f32x16 s0, s1, p0, p1;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[qb][i] = 0.f; pacc[qb][i] = 0.f; }
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-      for (int ks = 0; ks < DK; ++ks) {
-        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(Qb + tile_off<D>(32 * qb + l32, 16 * ks + 8 * hh));
-        const bf16x8 ag = *reinterpret_cast<const bf16x8*>(Gb + tile_off<D>(32 * qb + l32, 16 * ks + 8 * hh));
-        sacc[qb] = mfma32(aq, kf[ks], sacc[qb]);
-        pacc[qb] = mfma32(ag, vf[ks], pacc[qb]);
-      }
+    for (int ks = 0; ks < DK; ++ks) {
+      const bf16x8 aq0 = *reinterpret_cast<const bf16x8*>(Qb + q_off[ks]);
+      const bf16x8 aq1 = *reinterpret_cast<const bf16x8*>(Qb + q_off[ks] + 32 * D);
+      const bf16x8 ag0 = *reinterpret_cast<const bf16x8*>(Gb + q_off[ks]);
+      const bf16x8 ag1 = *reinterpret_cast<const bf16x8*>(Gb + q_off[ks] + 32 * D);
+      s0 = mfma32(aq0, kf[ks], ks == 0 ? zero16 : s0);
+      s1 = mfma32(aq1, kf[ks], ks == 0 ? zero16 : s1);
+      p0 = mfma32(ag0, vf[ks], ks == 0 ? zero16 : p0);
+      p1 = mfma32(ag1, vf[ks], ks == 0 ? zero16 : p1);
+    }
 
-    // ---- P = exp2(S c - LSE), dS = P (dP - D); masked entries give P = dS = 0 ----
-    // key index inside the segment of this lane's column, and the first query row of the tile:
-    // query row rr (counted from it.q_row0) sees key j iff j < it.n0 + rr.
-    const int jkey = it.j0 + 32 * wave + l32;
-    const int rr0 = qt * BM;
+    // ---- P = exp2(S c - LSE), dS = P (dP - D); entries a query does not see give P = dS = 0 ----
     bf16x8 pfrag[4], dsfrag[4];  // B operands per k-step of 16 queries
+    const int i0 = qt * BM;      // first query (inside the segment) of this tile
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      const bool need_mask = (it.j0 + 32 * wave + 31) >= (it.n0 + rr0 + 32 * qb);
+      const f32x16& s = qb == 0 ? s0 : s1;
+      const f32x16& dp = qb == 0 ? p0 : p1;
+      const bool need_mask = (i0 + 32 * qb) < (it.j0 + 32 * wave + 31 - it.ctx);
       float pv[16], dsv[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -240,26 +393,19 @@ __global__ __launch_bounds__(256) void bwd_main_kernel(BwdParams p) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int i = 4 * g + r;
-          float s = sacc[qb][i] * c - l4[r];
+          float pe = __builtin_amdgcn_exp2f(s[i] * c - l4[r]);
           if (need_mask) {
-            const int rr = rr0 + 32 * qb + 8 * g + 4 * hh + r;
-            if (jkey >= it.n0 + rr) s = -INFINITY;
+            const int qi = i0 + 32 * qb + 8 * g + 4 * hh + r;
+            if (qi < jrel) pe = 0.f;
           }
-          const float pe = __builtin_amdgcn_exp2f(s);
           pv[i] = pe;
-          dsv[i] = pe * (pacc[qb][i] - d4[r]);
+          dsv[i] = pe * (dp[i] - d4[r]);
         }
       }
       pfrag[2 * qb] = pack8(pv[0], pv[1], pv[2], pv[3], pv[4], pv[5], pv[6], pv[7]);
       pfrag[2 * qb + 1] = pack8(pv[8], pv[9], pv[10], pv[11], pv[12], pv[13], pv[14], pv[15]);
       dsfrag[2 * qb] = pack8(dsv[0], dsv[1], dsv[2], dsv[3], dsv[4], dsv[5], dsv[6], dsv[7]);
       dsfrag[2 * qb + 1] = pack8(dsv[8], dsv[9], dsv[10], dsv[11], dsv[12], dsv[13], dsv[14], dsv[15]);
-      // dS^T tile: row = key (32 wave + l32), columns = 4 consecutive queries per store
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const bf16x4 w = pack4(dsv[4 * g], dsv[4 * g + 1], dsv[4 * g + 2], dsv[4 * g + 3]);
-        *reinterpret_cast<bf16x4*>(dSt + (32 * wave + l32) * DSP + 32 * qb + 8 * g + 4 * hh) = w;
-      }
     }
 
     // ---- dV^T += dO^T P, dK^T += Q^T dS : [D] x [32 keys], contraction over the 64 queries ----
@@ -267,55 +413,19 @@ __global__ __launch_bounds__(256) void bwd_main_kernel(BwdParams p) {
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const bf16x8 ag = a_tr<D>(Gb, 16 * ks, 32 * db, lane);
-        const bf16x8 aq = a_tr<D>(Qb, 16 * ks, 32 * db, lane);
+        const bf16x8 ag = *reinterpret_cast<const bf16x8*>(GTb + t_off[ks] + db * 32 * BM);
+        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(QTb + t_off[ks] + db * 32 * BM);
         dvacc[db] = mfma32(ag, pfrag[ks], dvacc[db]);
         dkacc[db] = mfma32(aq, dsfrag[ks], dkacc[db]);
       }
 
-    __syncthreads();  // dS^T of all four waves is in LDS
-
-    // ---- dQ += dS K : [64 queries] x [D], contraction over the 128 keys; the 2 DB output blocks of
-    //      32 x 32 are dealt out to the four waves (block b: query block b % 2, column block b / 2) ----
-    {
-      constexpr int NB = 2 * DB / 4;
-      f32x16 dq[NB];
-#pragma unroll
-      for (int n = 0; n < NB; ++n)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dq[n][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < BN / 16; ++ks) {
-#pragma unroll
-        for (int n = 0; n < NB; ++n) {
-          const int b = wave * NB + n, qb = b & 1, db = b >> 1;
-          // B operand: K[key in C-order][column 32 db + l32], gathered with transpose reads
-          const bf16x8 bk = a_tr<D>(Kt, 16 * ks, 32 * db, lane);
-          // A operand: dS[query 32 qb + l32][key in C-order] from the dS^T tile
-          const int row = 16 * ks + 4 * hh + ((lane & 15) >> 2);
-          const int col = 32 * qb + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-          s16x4 lo = lds_read_tr(dSt + row * DSP + col);
-          s16x4 hi = lds_read_tr(dSt + (row + 8) * DSP + col);
-          s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          dq[n] = mfma32(__builtin_bit_cast(bf16x8, v), bk, dq[n]);
-        }
-      }
-      const int head = kvh * G + hg;
-      const int rows_left = it.q_rows - qt * BM;
-#pragma unroll
-      for (int n = 0; n < NB; ++n) {
-        const int b = wave * NB + n, qb = b & 1, db = b >> 1;
-        float* dqp = p.dq_acc + ((int64_t)it.q_row0 + qt * BM) * q_stride + (int64_t)head * D + 32 * db + l32;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = 32 * qb + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (r < rows_left) unsafeAtomicAdd(dqp + (int64_t)r * q_stride, dq[n][i]);
-        }
-      }
-    }
-
-    if (iter + 1 < n_iter) store_tiles(buf ^ 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+  };
+
+  for (int iter = 0; iter < n_iter; iter += 2) {
+    iter_step(iter, std::integral_constant<int, 0>{});
+    if (iter + 1 < n_iter) iter_step(iter + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- epilogue: dK = scale * dK^T, dV = dV^T, written (or added) as bf16 ----
@@ -345,106 +455,143 @@ __global__ __launch_bounds__(256) void bwd_main_kernel(BwdParams p) {
   }
 }
 
-template <int D>
-size_t bwd_smem_bytes_t() {
-  return (size_t)(tile_elems<D>(BN) + 4 * tile_elems<D>(BM) + BN * DSP) * 2 + 4 * BM * sizeof(float);
-}
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
-struct BwdLayout {
-  size_t dq_off, dsum_off, items_off, total;
-};
-BwdLayout bwd_layout(const chunk_attn_desc* d) {
-  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
-  BwdLayout L;
-  L.dq_off = 0;
-  const size_t dq_bytes = (size_t)d->total_q * d->num_q_heads * d->head_dim * sizeof(float);
-  L.dsum_off = up(dq_bytes);
-  const size_t dsum_bytes = (size_t)d->total_q * d->num_q_heads * sizeof(float);
-  L.items_off = L.dsum_off + up(dsum_bytes);
-  size_t n_items = 0;
-  for (int t = 0; t < d->num_segments; ++t) n_items += (d->segments[t].kv_len + BN - 1) / BN;
-  L.total = L.items_off + up(n_items * sizeof(BwdItem));
-  return L;
+template <class K>
+hipError_t set_smem(K kernel, size_t smem, bool* done) {
+  if (*done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)smem);
+  if (e == hipSuccess) *done = true;
+  return e;
 }
 
 template <int D>
-hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const std::vector<BwdItem>& items,
-                        hipStream_t stream) {
-  const BwdLayout L = bwd_layout(d);
-  float* dq_acc = reinterpret_cast<float*>(a.workspace + L.dq_off);
-  float* dsum = reinterpret_cast<float*>(a.workspace + L.dsum_off);
-  const int64_t n_pairs = (int64_t)d->total_q * d->num_q_heads;
+hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& P, hipStream_t stream) {
+  char* ws = a.workspace;
+  const TileJob* qjobs = reinterpret_cast<const TileJob*>(ws + P.qjobs_off);
+  const TileJob* kjobs = reinterpret_cast<const TileJob*>(ws + P.kjobs_off);
+  float* lse2p = reinterpret_cast<float*>(ws + P.lse2p_off);
+  float* dsp = reinterpret_cast<float*>(ws + P.dsp_off);
+  __bf16* qt = reinterpret_cast<__bf16*>(ws + P.qt_off);
+  __bf16* gt = reinterpret_cast<__bf16*>(ws + P.gt_off);
+  __bf16* kt = reinterpret_cast<__bf16*>(ws + P.kt_off);
+  hipError_t e;
 
-  {  // D = <dO, O>, dQ accumulator = 0
-    const int64_t threads = n_pairs * (D / 8);
-    hipLaunchKernelGGL((bwd_pre_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, a.o, a.d_o,
-                       dsum, dq_acc, d->total_q, d->num_q_heads);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+  // pre-pass: D, scaled LSE, transposed operand images
+  {
+    const int64_t blocks = (int64_t)P.qjobs.size() * d->num_q_heads;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_pre_kernel<D>), dim3((unsigned)blocks), dim3(256), 0, stream, a.o, a.d_o, a.lse, qjobs,
+                       P.q_tiles, d->total_q, d->num_q_heads, lse2p, dsp);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
   }
+  if ((e = launch_transpose(a.q, d->num_q_heads, D, 64, qjobs, (int)P.qjobs.size(), P.q_tiles, qt, stream)) != hipSuccess) return e;
+  if ((e = launch_transpose(a.d_o, d->num_q_heads, D, 64, qjobs, (int)P.qjobs.size(), P.q_tiles, gt, stream)) != hipSuccess) return e;
+  if ((e = launch_transpose(a.k, d->num_kv_heads, D, 32, kjobs, (int)P.kjobs.size(), P.kv32_tiles, kt, stream)) != hipSuccess) return e;
+
   if (!a.accumulate) {  // rows no segment covers receive no gradient
     for (const auto& gap : uncovered_kv_ranges(d)) {
-      const int64_t elems = (int64_t)(gap.second - gap.first) * d->num_kv_heads * D;
-      const int64_t n16 = elems / 8;
+      const int64_t n16 = (int64_t)(gap.second - gap.first) * d->num_kv_heads * D / 8;
       for (__bf16* base : {a.dk, a.dv}) {
         u32x4* ptr = reinterpret_cast<u32x4*>(base + (int64_t)gap.first * d->num_kv_heads * D);
         hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, stream, ptr, n16);
       }
-      hipError_t e = hipGetLastError();
-      if (e != hipSuccess) return e;
+      if ((e = hipGetLastError()) != hipSuccess) return e;
     }
   }
-  {
-    BwdParams p;
-    p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.lse = a.lse; p.dsum = dsum;
-    p.dq_acc = dq_acc; p.dk = a.dk; p.dv = a.dv;
-    p.items = reinterpret_cast<const BwdItem*>(a.workspace + L.items_off);
-    p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = d->num_q_heads / d->num_kv_heads;
-    p.total_q = d->total_q;
-    p.scale = d->softmax_scale;
-    p.scale_log2 = d->softmax_scale * 1.4426950408889634f;
+
+  const int group = d->num_q_heads / d->num_kv_heads;
+  {  // dQ
+    DqParams p;
+    p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.kt = kt; p.lse2p = lse2p; p.dsp = dsp; p.dq = a.dq;
+    p.items = reinterpret_cast<const DqItem*>(ws + P.dq_items_off);
+    p.total_kv32_tiles = P.kv32_tiles; p.total_q_tiles = P.q_tiles;
+    p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
+    p.heads_per_wg = fwd_heads_per_wg(group); p.head_splits = group / p.heads_per_wg;
+    p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
+    const size_t smem = (size_t)6 * 32 * D * 2;
+    static bool attr = false;
+    if ((e = set_smem(&bwd_dq_kernel<D>, smem, &attr)) != hipSuccess) return e;
+    const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_dq_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {  // dK, dV
+    DkvParams p;
+    p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.qt = qt; p.gt = gt; p.lse2p = lse2p; p.dsp = dsp;
+    p.dk = a.dk; p.dv = a.dv;
+    p.items = reinterpret_cast<const DkvItem*>(ws + P.dkv_items_off);
+    p.total_q_tiles = P.q_tiles;
+    p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
+    p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
-    const size_t smem = bwd_smem_bytes_t<D>();
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_main_kernel<D>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
-    const int64_t blocks = (int64_t)items.size() * d->num_kv_heads;
+    const size_t smem = (size_t)8 * 64 * D * 2 + 4 * 64 * sizeof(float);
+    static bool attr = false;
+    if ((e = set_smem(&bwd_dkv_kernel<D>, smem, &attr)) != hipSuccess) return e;
+    const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     ProfileEvents pe = profile_events();
     profile_events() = ProfileEvents{};
-    hipError_t e;
     if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_main_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_dkv_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return e;
-  }
-  {
-    const int64_t n8 = n_pairs * (D / 8);
-    hipLaunchKernelGGL((bwd_post_kernel<D>), dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, dq_acc, a.dq, n8,
-                       d->softmax_scale);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
 }  // namespace
 
-size_t bwd_workspace_bytes(const chunk_attn_desc* d) { return bwd_layout(d).total; }
-
-void bwd_prepare(const chunk_attn_desc* d, std::vector<BwdItem>& items, size_t* items_off) {
-  items = plan_bwd(d, BN);
-  *items_off = bwd_layout(d).items_off;
+void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
+  const int group = d->num_q_heads / d->num_kv_heads;
+  const int dq_rows = fwd_tile_rows(group);
+  P.q_tiles = count_tiles(d, false, 64);
+  P.kv32_tiles = count_tiles(d, true, 32);
+  size_t n_dq = 0, n_dkv = 0;
+  if (with_plan) {
+    P.dq_items = plan_dq(d, dq_rows);
+    P.dkv_items = plan_dkv(d);
+    P.qjobs = tile_jobs(d, false, 64, nullptr);
+    P.kjobs = tile_jobs(d, true, 32, nullptr);
+    n_dq = P.dq_items.size();
+    n_dkv = P.dkv_items.size();
+  } else {
+    for (int t = 0; t < d->num_segments; ++t) {
+      n_dq += (d->segments[t].q_len + dq_rows - 1) / dq_rows;
+      n_dkv += (d->segments[t].kv_len + 127) / 128;
+    }
+  }
+  P.dq_items_off = 0;
+  P.dkv_items_off = up256(n_dq * sizeof(DqItem));
+  P.qjobs_off = P.dkv_items_off + up256(n_dkv * sizeof(DkvItem));
+  P.kjobs_off = P.qjobs_off + up256((size_t)P.q_tiles * sizeof(TileJob));
+  P.blob_bytes = P.kjobs_off + up256((size_t)P.kv32_tiles * sizeof(TileJob));
+  const size_t row_slots = (size_t)d->num_q_heads * P.q_tiles * 64;
+  P.lse2p_off = P.blob_bytes;
+  P.dsp_off = P.lse2p_off + up256(row_slots * sizeof(float));
+  P.qt_off = P.dsp_off + up256(row_slots * sizeof(float));
+  const size_t qimg = up256(row_slots * d->head_dim * sizeof(__bf16));
+  P.gt_off = P.qt_off + qimg;
+  P.kt_off = P.gt_off + qimg;
+  P.total = P.kt_off + up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16));
 }
 
-hipError_t launch_bwd(const chunk_attn_desc* d, const BwdArgs& a, const std::vector<BwdItem>& items,
-                      hipStream_t stream) {
-  return d->head_dim == 128 ? launch_bwd_t<128>(d, a, items, stream) : launch_bwd_t<64>(d, a, items, stream);
+std::vector<char> bwd_blob(const BwdPlan& P) {
+  std::vector<char> blob(P.blob_bytes);
+  std::memcpy(blob.data() + P.dq_items_off, P.dq_items.data(), P.dq_items.size() * sizeof(DqItem));
+  std::memcpy(blob.data() + P.dkv_items_off, P.dkv_items.data(), P.dkv_items.size() * sizeof(DkvItem));
+  std::memcpy(blob.data() + P.qjobs_off, P.qjobs.data(), P.qjobs.size() * sizeof(TileJob));
+  std::memcpy(blob.data() + P.kjobs_off, P.kjobs.data(), P.kjobs.size() * sizeof(TileJob));
+  return blob;
+}
+
+hipError_t launch_bwd(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& P, hipStream_t stream) {
+  return d->head_dim == 128 ? launch_bwd_t<128>(d, a, P, stream) : launch_bwd_t<64>(d, a, P, stream);
 }
 
 }  // namespace chunk_attn

@@ -33,22 +33,6 @@ struct ProfileEvents {
 };
 ProfileEvents& profile_events();
 
-struct BwdParams {
-  const __bf16* q;
-  const __bf16* k;
-  const __bf16* v;
-  const __bf16* d_o;
-  const float* lse;
-  const float* dsum;  // D_i = <dO_i, O_i>, [Hq][total_q]
-  float* dq_acc;      // float32 [total_q][Hq][D], unscaled
-  __bf16* dk;
-  __bf16* dv;
-  const BwdItem* items;
-  int32_t num_q_heads, num_kv_heads, group, total_q;
-  float scale, scale_log2;
-  int32_t accumulate;
-};
-
 // Pointers of one backward call (device memory, caller-owned).
 struct BwdArgs {
   const __bf16 *q, *k, *v, *o, *d_o;
@@ -58,17 +42,29 @@ struct BwdArgs {
   char* workspace;
 };
 
-size_t bwd_workspace_bytes(const chunk_attn_desc* d);
-// Builds the backward schedule and reports where in the workspace it has to be uploaded.
-void bwd_prepare(const chunk_attn_desc* d, std::vector<BwdItem>& items, size_t* items_off);
-// Enqueues the backward kernels; the schedule must already be on its way to the workspace on `stream`.
-hipError_t launch_bwd(const chunk_attn_desc* d, const BwdArgs& a, const std::vector<BwdItem>& items,
-                      hipStream_t stream);
+// Host-side plan of one backward call and the layout of its workspace:
+// [dQ items | dK/dV items | query-tile jobs | key-tile jobs] (one uploaded blob), then the padded
+// LSE and D arrays and the transposed images of Q, dO (64-row tiles) and K (32-row tiles).
+struct BwdPlan {
+  std::vector<DqItem> dq_items;
+  std::vector<DkvItem> dkv_items;
+  std::vector<TileJob> qjobs, kjobs;
+  int64_t q_tiles = 0, kv32_tiles = 0;
+  size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, blob_bytes = 0;
+  size_t lse2p_off = 0, dsp_off = 0, qt_off = 0, gt_off = 0, kt_off = 0, total = 0;
+};
+// Fills the offsets (and, if with_plan, the schedules) for a validated descriptor.
+void bwd_layout(const chunk_attn_desc* d, BwdPlan& plan, bool with_plan);
+// The host image of the blob at the start of the workspace.
+std::vector<char> bwd_blob(const BwdPlan& plan);
+// Enqueues the backward kernels; the blob must already be on its way to the workspace on `stream`.
+hipError_t launch_bwd(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& plan, hipStream_t stream);
 
 hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, hipStream_t stream);
 
-// Transposed 64-row tile images of x[rows][num_heads][head_dim]: out[num_heads][total_tiles][head_dim][64].
-hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, const TileJob* jobs, int num_jobs,
+// Transposed tile images (width 64 or 32 rows) of x[rows][num_heads][head_dim]:
+// out[num_heads][total_tiles][head_dim][width].
+hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, int width, const TileJob* jobs, int num_jobs,
                             int64_t total_tiles, __bf16* out, hipStream_t stream);
 
 }  // namespace chunk_attn

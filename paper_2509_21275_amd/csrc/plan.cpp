@@ -36,23 +36,24 @@ int64_t pair_count(const chunk_attn_desc* d) {
   return n;
 }
 
-int64_t count_tiles(const chunk_attn_desc* d, bool kv) {
+int64_t count_tiles(const chunk_attn_desc* d, bool kv, int width) {
   int64_t n = 0;
-  for (int t = 0; t < d->num_segments; ++t) n += ((kv ? d->segments[t].kv_len : d->segments[t].q_len) + 63) / 64;
+  for (int t = 0; t < d->num_segments; ++t)
+    n += ((kv ? d->segments[t].kv_len : d->segments[t].q_len) + width - 1) / width;
   return n;
 }
 
-std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, std::vector<int32_t>* seg_tile0) {
+std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, int width, std::vector<int32_t>* seg_tile0) {
   std::vector<TileJob> jobs;
   if (seg_tile0) seg_tile0->clear();
   for (int t = 0; t < d->num_segments; ++t) {
     const chunk_attn_seg& s = d->segments[t];
     const int32_t start = kv ? s.kv_start : s.q_start, len = kv ? s.kv_len : s.q_len;
     if (seg_tile0) seg_tile0->push_back((int32_t)jobs.size());
-    for (int32_t r = 0; r < len; r += 64) {
+    for (int32_t r = 0; r < len; r += width) {
       TileJob j;
       j.src_row0 = start + r;
-      j.valid_rows = std::min<int32_t>(64, len - r);
+      j.valid_rows = std::min<int32_t>(width, len - r);
       j.image = (int32_t)jobs.size();
       j.pad = 0;
       jobs.push_back(j);
@@ -85,25 +86,56 @@ std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows) {
   return items;
 }
 
-std::vector<BwdItem> plan_bwd(const chunk_attn_desc* d, int tile_rows) {
-  std::vector<BwdItem> items;
+std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows) {
+  std::vector<DqItem> items;
+  int32_t kv_tile0 = 0, q_tile0 = 0;
   for (int t = 0; t < d->num_segments; ++t) {
     const chunk_attn_seg& s = d->segments[t];
     const int32_t C = s.kv_len - s.q_len;
-    for (int32_t j0 = 0; j0 < s.kv_len; j0 += tile_rows) {
-      BwdItem it{};
-      it.kv_row0 = s.kv_start + j0;
-      it.kv_rows = std::min<int32_t>(tile_rows, s.kv_len - j0);
-      const int32_t i_first = std::max<int32_t>(0, j0 - C);  // first query that sees key j0
-      it.q_row0 = s.q_start + i_first;
-      it.q_rows = s.q_len - i_first;
-      it.n0 = C + i_first + 1;
-      it.j0 = j0;
+    for (int32_t i0 = 0; i0 < s.q_len; i0 += tile_rows) {
+      DqItem it{};
+      it.q_row0 = s.q_start + i0;
+      it.q_rows = std::min<int32_t>(tile_rows, s.q_len - i0);
+      it.kv_row0 = s.kv_start;
+      it.n0 = C + i0 + 1;
+      it.kv_tile0 = kv_tile0;
+      it.q_slot0 = q_tile0 * 64 + i0;
       items.push_back(it);
     }
+    kv_tile0 += (s.kv_len + 31) / 32;
+    q_tile0 += (s.q_len + 63) / 64;
   }
-  std::stable_sort(items.begin(), items.end(),
-                   [](const BwdItem& a, const BwdItem& b) { return a.q_rows > b.q_rows; });
+  std::stable_sort(items.begin(), items.end(), [](const DqItem& a, const DqItem& b) {
+    return (int64_t)a.n0 + a.q_rows > (int64_t)b.n0 + b.q_rows;
+  });
+  return items;
+}
+
+std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d) {
+  std::vector<DkvItem> items;
+  int32_t q_tile0 = 0;
+  for (int t = 0; t < d->num_segments; ++t) {
+    const chunk_attn_seg& s = d->segments[t];
+    const int32_t C = s.kv_len - s.q_len;
+    const int32_t n_qt = (s.q_len + 63) / 64;
+    for (int32_t j0 = 0; j0 < s.kv_len; j0 += 128) {
+      DkvItem it{};
+      it.kv_row0 = s.kv_start + j0;
+      it.kv_rows = std::min<int32_t>(128, s.kv_len - j0);
+      it.j0 = j0;
+      it.ctx = C;
+      it.q_row_seg = s.q_start;
+      it.q_len = s.q_len;
+      it.qt_first = std::max<int32_t>(0, j0 - C) / 64;  // query i sees key j0 iff i >= j0 - C
+      it.n_qt = n_qt;
+      it.q_tile0 = q_tile0;
+      items.push_back(it);
+    }
+    q_tile0 += n_qt;
+  }
+  std::stable_sort(items.begin(), items.end(), [](const DkvItem& a, const DkvItem& b) {
+    return a.n_qt - a.qt_first > b.n_qt - b.qt_first;
+  });
   return items;
 }
 

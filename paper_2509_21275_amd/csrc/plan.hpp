@@ -13,7 +13,7 @@
 
 namespace chunk_attn {
 
-// A 64-row tile of a tensor to be transposed by the pre-pass: rows [src_row0, src_row0 + valid_rows).
+// A tile (64 or 32 rows) of a tensor to be transposed by the pre-pass: rows [src_row0, src_row0 + valid_rows).
 struct TileJob {
   int32_t src_row0, valid_rows;
   int32_t image;  // index of the output image (per head)
@@ -30,15 +30,30 @@ struct FwdItem {
   int32_t pad0, pad1, pad2;
 };
 
-// Backward work item: a tile of consecutive key rows of one segment and the queries that see it.
-struct BwdItem {
-  int32_t kv_row0;  // first key row of the tile (global)
-  int32_t kv_rows;  // valid key rows in the tile (>= 1)
-  int32_t q_row0;   // first query row (global) that sees any key of the tile
-  int32_t q_rows;   // queries from q_row0 to the end of the segment (>= 1)
-  int32_t n0;       // keys of the segment visible to query q_row0, counted from the segment's first key
-  int32_t j0;       // index of the tile's first key inside the segment
+// Work item of the dQ kernel: a tile of consecutive query rows of one segment (as in the forward).
+struct DqItem {
+  int32_t q_row0;    // first query row (global)
+  int32_t q_rows;    // valid rows in the tile (>= 1)
+  int32_t kv_row0;   // first key row of the segment (global)
+  int32_t n0;        // keys visible to the tile's first row
+  int32_t kv_tile0;  // index of the transposed image of the segment's first 32-key tile
+  int32_t q_slot0;   // slot of the tile's first row in the padded per-row arrays (LSE, D)
   int32_t pad0, pad1;
+};
+
+// Work item of the dK/dV kernel: 128 consecutive key rows of one segment and the 64-row query tiles
+// (aligned to the segment's first query) that contain at least one query seeing them.
+struct DkvItem {
+  int32_t kv_row0;    // first key row of the tile (global)
+  int32_t kv_rows;    // valid key rows (1..128)
+  int32_t j0;         // index of the tile's first key inside the segment
+  int32_t ctx;        // context length C of the segment
+  int32_t q_row_seg;  // first query row of the segment (global)
+  int32_t q_len;      // queries in the segment
+  int32_t qt_first;   // first 64-row query tile (inside the segment) that sees a key of this tile
+  int32_t n_qt;       // number of 64-row query tiles of the segment
+  int32_t q_tile0;    // image / slot index of the segment's first query tile
+  int32_t pad0, pad1, pad2;
 };
 
 int validate(const chunk_attn_desc* d);
@@ -46,12 +61,12 @@ int64_t pair_count(const chunk_attn_desc* d);
 
 // Tiles of `tile_rows` query rows per segment, most work first.
 std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows);
-// Tiles of `tile_rows` key rows per segment, most work first.
-std::vector<BwdItem> plan_bwd(const chunk_attn_desc* d, int tile_rows);
-// 64-row tiles of every segment's key range (kv = true) or query range (kv = false), in segment order;
+std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows);
+std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d);
+// `width`-row tiles of every segment's key range (kv = true) or query range (kv = false), in segment order;
 // seg_tile0[t] receives the image index of segment t's first tile.
-std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, std::vector<int32_t>* seg_tile0);
-int64_t count_tiles(const chunk_attn_desc* d, bool kv);
+std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, int width, std::vector<int32_t>* seg_tile0);
+int64_t count_tiles(const chunk_attn_desc* d, bool kv, int width);
 // Key-row ranges [begin, end) not covered by any segment (to be zero-filled when not accumulating).
 std::vector<std::pair<int32_t, int32_t>> uncovered_kv_ranges(const chunk_attn_desc* d);
 

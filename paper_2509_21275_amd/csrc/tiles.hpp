@@ -18,10 +18,13 @@ __device__ __forceinline__ int swz(int row, int c) {
     // 256-byte rows: rotate by a 4x4 bit-transposed row index; conflict-free for 16 consecutive rows
     const int f = ((row & 3) << 2) | ((row >> 2) & 3);
     return (c + f) & 15;
-  } else {
-    static_assert(CHUNKS == 8, "tiles have 8 or 16 chunks per row");
+  } else if constexpr (CHUNKS == 8) {
     // 128-byte rows: two rows share a 256-byte bank line, so the permutation changes every other row
     return c ^ ((row >> 1) & 7);
+  } else {
+    static_assert(CHUNKS == 4, "tiles have 4, 8 or 16 chunks per row");
+    // 64-byte rows: four rows share a bank line
+    return c ^ ((row >> 2) & 3);
   }
 }
 // logical chunk stored at physical position pc (inverse of swz)
@@ -30,8 +33,10 @@ __device__ __forceinline__ int unswz(int row, int pc) {
   if constexpr (CHUNKS == 16) {
     const int f = ((row & 3) << 2) | ((row >> 2) & 3);
     return (pc - f) & 15;
-  } else {
+  } else if constexpr (CHUNKS == 8) {
     return pc ^ ((row >> 1) & 7);
+  } else {
+    return pc ^ ((row >> 2) & 3);
   }
 }
 // element offset of (row, logical chunk c) in a swizzled tile
@@ -40,6 +45,10 @@ __device__ __forceinline__ int tile_elem(int row, int c) {
   return (row * CHUNKS + swz<CHUNKS>(row, c)) * 8;
 }
 
+__device__ __forceinline__ void dma4(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
+}
 __device__ __forceinline__ void dma16(const void* gsrc, void* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);

@@ -1,7 +1,7 @@
 // Pre-pass that prepares transposed operand tiles.
 //
-// For X[rows][H][D] (bf16) and a list of 64-row tiles, writes for every (head, tile) an "image"
-// T[D][64] with T[c][p] = X[row0 + cperm(p)][head][c] (zero past the tile's valid rows), already in
+// For X[rows][H][D] (bf16) and a list of W-row tiles (W = 64 or 32), writes for every (head, tile) an "image"
+// T[D][W] with T[c][p] = X[row0 + cperm(p)][head][c] (zero past the tile's valid rows), already in
 // the swizzled chunk order in which the attention kernels keep it in LDS.  The attention kernels then
 // fetch an image with a linear global->LDS copy and read MFMA operands whose contraction index runs
 // along X's row index (V^T for O += P V, K^T for dQ += dS K, Q^T and dO^T for dK, dV) with plain
@@ -11,17 +11,17 @@
 
 namespace chunk_attn {
 
-template <int D>
+template <int D, int W>
 __global__ __launch_bounds__(256) void transpose_tiles_kernel(const __bf16* __restrict__ x, int num_heads,
                                                               const TileJob* __restrict__ jobs, int64_t total_tiles,
                                                               __bf16* __restrict__ out) {
   constexpr int P = D + 2;  // LDS pitch (elements) of the staging tile
-  __shared__ __bf16 stage[64 * P];
+  __shared__ __bf16 stage[W * P];
   const int tid = threadIdx.x;
   const int h = blockIdx.x % num_heads;
   const TileJob job = jobs[blockIdx.x / num_heads];
   const int64_t stride = (int64_t)num_heads * D;
-  for (int idx = tid; idx < 64 * (D / 8); idx += 256) {
+  for (int idx = tid; idx < W * (D / 8); idx += 256) {
     const int row = idx / (D / 8), c = idx % (D / 8);
     bf16x8 v;
 #pragma unroll
@@ -31,10 +31,11 @@ __global__ __launch_bounds__(256) void transpose_tiles_kernel(const __bf16* __re
     for (int i = 0; i < 8; ++i) stage[row * P + c * 8 + i] = v[i];
   }
   __syncthreads();
-  __bf16* img = out + ((int64_t)h * total_tiles + job.image) * (D * 64);
-  for (int idx = tid; idx < D * 8; idx += 256) {
-    const int d = idx / 8, pc = idx % 8;
-    const int c = unswz<8>(d, pc);
+  __bf16* img = out + ((int64_t)h * total_tiles + job.image) * (D * W);
+  constexpr int WC = W / 8;
+  for (int idx = tid; idx < D * WC; idx += 256) {
+    const int d = idx / WC, pc = idx % WC;
+    const int c = unswz<WC>(d, pc);
     bf16x8 v;
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = stage[cperm(8 * c + i) * P + d];
@@ -42,17 +43,23 @@ __global__ __launch_bounds__(256) void transpose_tiles_kernel(const __bf16* __re
   }
 }
 
-hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, const TileJob* jobs, int num_jobs,
+template <int D, int W>
+static void launch_t(const __bf16* x, int num_heads, const TileJob* jobs, int64_t blocks, int64_t total_tiles,
+                     __bf16* out, hipStream_t stream) {
+  hipLaunchKernelGGL((transpose_tiles_kernel<D, W>), dim3((unsigned)blocks), dim3(256), 0, stream, x, num_heads, jobs,
+                     total_tiles, out);
+}
+
+hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, int width, const TileJob* jobs, int num_jobs,
                             int64_t total_tiles, __bf16* out, hipStream_t stream) {
   if (num_jobs == 0) return hipSuccess;
   const int64_t blocks = (int64_t)num_jobs * num_heads;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-  if (head_dim == 128)
-    hipLaunchKernelGGL((transpose_tiles_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, stream, x, num_heads, jobs,
-                       total_tiles, out);
-  else
-    hipLaunchKernelGGL((transpose_tiles_kernel<64>), dim3((unsigned)blocks), dim3(256), 0, stream, x, num_heads, jobs,
-                       total_tiles, out);
+  if (head_dim == 128 && width == 64) launch_t<128, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream);
+  else if (head_dim == 128 && width == 32) launch_t<128, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream);
+  else if (head_dim == 64 && width == 64) launch_t<64, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream);
+  else if (head_dim == 64 && width == 32) launch_t<64, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
