@@ -90,14 +90,17 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
   constexpr int DB = D / 32;   // 32-row blocks of dQ^T
   constexpr int KT = BN * D;   // elements per tile
 
+  constexpr int NS = 3;        // LDS stages: tiles are fetched NS - 1 iterations ahead
+
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  __bf16* Ks = reinterpret_cast<__bf16*>(smem);  // [2][BN][D]
-  __bf16* Vs = Ks + 2 * KT;                      // [2][BN][D]
-  __bf16* Ts = Vs + 2 * KT;                      // [2][D][BN]  K^T image
+  __bf16* Ks = reinterpret_cast<__bf16*>(smem);  // [NS][BN][D]
+  __bf16* Vs = Ks + NS * KT;                     // [NS][BN][D]
+  __bf16* Ts = Vs + NS * KT;                     // [NS][D][BN]  K^T image
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
+  stagger_wave_priority();
 
   const int inner_n = p.num_kv_heads * p.head_splits;
   const int inner = blockIdx.x % inner_n;
@@ -128,23 +131,26 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
     k_row[i] = x / KC;
     k_src[i] = (unsigned)(k_row[i] * (int)kv_stride + unswz<KC>(k_row[i], x % KC) * 8);
   }
-  auto dma_tile = [&](int t, int buf) {
-    const int64_t toff = (int64_t)(BN * t) * kv_stride;  // wave-uniform
-    const int last_row = n_wg - 1 - BN * t;
-#pragma unroll
-    for (int i = 0; i < NK; ++i) {
+  // One tile is copied by NK + NT pieces per lane (piece i < NK: a K and a V chunk; else a K^T image chunk), so
+  // that the copies can be issued between MFMAs instead of in one burst.
+  auto dma_piece = [&](int t, int buf, int i) {
+    if (i < NK) {
+      const int64_t toff = (int64_t)(BN * t) * kv_stride;  // wave-uniform
+      const int last_row = n_wg - 1 - BN * t;
       unsigned off = k_src[i];
       if (last_row < BN - 1) off -= (unsigned)((k_row[i] - min(k_row[i], last_row)) * (int)kv_stride);
       dma16(Kg + toff + off, Ks + buf * KT + (i * 4 + wave) * 512);
       dma16(Vg + toff + off, Vs + buf * KT + (i * 4 + wave) * 512);
+    } else {
+      const int j = i - NK;
+      const __bf16* tsrc = Timg + (int64_t)t * KT;
+      dma16(tsrc + (unsigned)(((j * 4 + wave) * 64 + lane) * 8), Ts + buf * KT + (j * 4 + wave) * 512);
     }
-    const __bf16* tsrc = Timg + (int64_t)t * KT;
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
-      dma16(tsrc + (unsigned)(((i * 4 + wave) * 64 + lane) * 8), Ts + buf * KT + (i * 4 + wave) * 512);
   };
-
-  dma_tile(0, 0);
+  auto dma_tile = [&](int t, int buf) {
+#pragma unroll
+    for (int i = 0; i < NK + NT; ++i) dma_piece(t, buf, i);
+  };
 
   // Q and dO fragments (B operands): lane holds X[row = l32][16 ks + 8 hh ..+7]
   bf16x8 qf[DK], gf[DK];
@@ -160,6 +166,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
   const int64_t slot = (int64_t)head * p.total_q_tiles * 64 + it.q_slot0 + r_own;
   const float lse2 = p.lse2p[slot], dsum = p.dsp[slot];
 
+  // prologue: the first NS - 1 tiles (issued after the register loads so that vmcnt below counts only copies)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nt_wg) dma_tile(s, s);
+
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 dq[DB];
 #pragma unroll
@@ -172,25 +184,54 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) t_off[ks] = tile_elem<4>(l32, 2 * ks + hh);
 
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+  // wait until at most `tiles_in_flight` later tiles are still being copied (each is NK * 2 + NT copies per lane)
+  auto wait_tiles = [&](int tiles_in_flight) {
+    constexpr int PER = 2 * NK + NT;
+    if (tiles_in_flight <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER) : "memory");
+  };
+  wait_tiles(min(nt_wg, NS - 1) - 1);
+  wg_barrier();
 
   auto tile_step = [&](int t, auto buf_c) {
     constexpr int buf = decltype(buf_c)::value;
-    if (t + 1 < nt_wg) dma_tile(t + 1, buf ^ 1);
+    const bool prefetch = t + NS - 1 < nt_wg;
+    if (t >= nt_w && prefetch) dma_tile(t + NS - 1, (buf + NS - 1) % NS);  // idle wave: still does its share of the copies
 
     if (t < nt_w) {
       const __bf16* Kt = Ks + buf * KT;
       const __bf16* Vt = Vs + buf * KT;
       const __bf16* Tt = Ts + buf * KT;
+      // The loop body is laid out as stages separated by scheduling fences: each stage issues the LDS reads
+      // of the next stage's operands together with the MFMAs of the current one, so the reads' latency is
+      // covered by matrix work instead of stalling every MFMA on the read issued just before it.
+      auto ldk = [&](int ks) { return *reinterpret_cast<const bf16x8*>(Kt + k_off[ks]); };
+      auto ldv = [&](int ks) { return *reinterpret_cast<const bf16x8*>(Vt + k_off[ks]); };
       // ---- S^T = K Q^T, dP^T = V dO^T : [32 keys] x [32 queries] ----
       f32x16 s, dp;
+      bf16x8 ak[2][2], av[2][2];  // [parity of the k-step pair][step in the pair]
+      ak[0][0] = ldk(0); av[0][0] = ldv(0); ak[0][1] = ldk(1); av[0][1] = ldv(1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < DK; ++ks) {
-        const bf16x8 ak = *reinterpret_cast<const bf16x8*>(Kt + k_off[ks]);
-        const bf16x8 av = *reinterpret_cast<const bf16x8*>(Vt + k_off[ks]);
-        s = mfma32(ak, qf[ks], ks == 0 ? zero16 : s);
-        dp = mfma32(av, gf[ks], ks == 0 ? zero16 : dp);
+      for (int g = 0; g < DK / 2; ++g) {
+        const int cur = g & 1, nxt = cur ^ 1;
+        if (g + 1 < DK / 2) {
+          ak[nxt][0] = ldk(2 * g + 2); av[nxt][0] = ldv(2 * g + 2);
+          ak[nxt][1] = ldk(2 * g + 3); av[nxt][1] = ldv(2 * g + 3);
+        }
+        s = mfma32(ak[cur][0], qf[2 * g], g == 0 ? zero16 : s);
+        dp = mfma32(av[cur][0], gf[2 * g], g == 0 ? zero16 : dp);
+        if (prefetch && g < NK + NT) dma_piece(t + NS - 1, (buf + NS - 1) % NS, g);
+        s = mfma32(ak[cur][1], qf[2 * g + 1], s);
+        dp = mfma32(av[cur][1], gf[2 * g + 1], dp);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // operands of dQ^T += K^T dS^T, fetched while the exponentials are computed
+      bf16x8 at[2][DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        at[0][db] = *reinterpret_cast<const bf16x8*>(Tt + t_off[0] + db * 32 * BN);
+        at[1][db] = *reinterpret_cast<const bf16x8*>(Tt + t_off[1] + db * 32 * BN);
       }
       // ---- P = exp2(S c - LSE), dS = P (dP - D); masked keys give P = 0 ----
       float pe[16];
@@ -209,23 +250,22 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
       for (int i = 0; i < 16; ++i) ds[i] = pe[i] * (dp[i] - dsum);
       const bf16x8 f0 = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
       const bf16x8 f1 = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+      __builtin_amdgcn_sched_barrier(0);
       // ---- dQ^T += K^T dS^T : [D] x [32 queries], contraction over the 32 keys ----
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Tt + t_off[0] + db * 32 * BN);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Tt + t_off[1] + db * 32 * BN);
-        dq[db] = mfma32(a0, f0, dq[db]);
-        dq[db] = mfma32(a1, f1, dq[db]);
-      }
+      for (int db = 0; db < DB; ++db) dq[db] = mfma32(at[0][db], f0, dq[db]);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) dq[db] = mfma32(at[1][db], f1, dq[db]);
     }
-
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    // tile t + 1 must have landed; tiles t + 2 .. may still be in flight
+    wait_tiles(min(nt_wg - 1, t + NS - 1) - (t + 1));
+    wg_barrier();
   };
 
-  for (int t = 0; t < nt_wg; t += 2) {
+  for (int t = 0; t < nt_wg; t += NS) {
     tile_step(t, std::integral_constant<int, 0>{});
     if (t + 1 < nt_wg) tile_step(t + 1, std::integral_constant<int, 1>{});
+    if (t + 2 < nt_wg) tile_step(t + 2, std::integral_constant<int, 2>{});
   }
 
   // ---- epilogue: dQ = scale * dQ^T ----
@@ -318,27 +358,40 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(DkvParams p) {
     q_row[i] = x / KC;
     q_src[i] = (unsigned)(q_row[i] * (int)q_stride + unswz<KC>(q_row[i], x % KC) * 8);
   }
-  auto dma_stage = [&](int iter, int buf) {
+  // The copies of one (head, query tile) stage are split into NQ + NI pieces per lane (piece i < NQ: a Q and a dO
+  // row chunk; else a Q^T and a dO^T image chunk), so that they can be issued between MFMAs.
+  struct StageSrc { int64_t roff, tile; int last_row; };
+  auto stage_src = [&](int iter) {
     const int hg = iter / nqt, qt = it.qt_first + iter % nqt;
     const int head = kvh * G + hg;
-    const int last_row = it.q_len - 1 - qt * BM;  // >= 0
-    const int64_t roff = (int64_t)(it.q_row_seg + qt * BM) * q_stride + (int64_t)head * D;  // wave-uniform
-#pragma unroll
-    for (int i = 0; i < NQ; ++i) {
+    StageSrc ss;
+    ss.last_row = it.q_len - 1 - qt * BM;  // >= 0
+    ss.roff = (int64_t)(it.q_row_seg + qt * BM) * q_stride + (int64_t)head * D;  // wave-uniform
+    ss.tile = (int64_t)head * p.total_q_tiles + it.q_tile0 + qt;                  // wave-uniform
+    return ss;
+  };
+  auto dma_piece = [&](const StageSrc& ss, int buf, int i) {
+    if (i < NQ) {
       unsigned off = q_src[i];
-      if (last_row < BM - 1) off -= (unsigned)((q_row[i] - min(q_row[i], last_row)) * (int)q_stride);
-      dma16(p.q + roff + off, Qs + buf * QT + (i * 4 + wave) * 512);
-      dma16(p.d_o + roff + off, Gs + buf * QT + (i * 4 + wave) * 512);
+      if (ss.last_row < BM - 1) off -= (unsigned)((q_row[i] - min(q_row[i], ss.last_row)) * (int)q_stride);
+      dma16(p.q + ss.roff + off, Qs + buf * QT + (i * 4 + wave) * 512);
+      dma16(p.d_o + ss.roff + off, Gs + buf * QT + (i * 4 + wave) * 512);
+    } else {
+      const int j = i - NQ;
+      const unsigned off = (unsigned)(((j * 4 + wave) * 64 + lane) * 8);
+      dma16(p.qt + ss.tile * QT + off, QTs + buf * QT + (j * 4 + wave) * 512);
+      dma16(p.gt + ss.tile * QT + off, GTs + buf * QT + (j * 4 + wave) * 512);
     }
-    const int64_t tile = (int64_t)head * p.total_q_tiles + it.q_tile0 + qt;  // wave-uniform
+  };
+  auto dma_rowvals = [&](const StageSrc& ss, int buf) {
+    if (wave == 0) dma4(p.lse2p + ss.tile * 64 + lane, lse_s + buf * BM);
+    if (wave == 1) dma4(p.dsp + ss.tile * 64 + lane, dsum_s + buf * BM);
+  };
+  auto dma_stage = [&](int iter, int buf) {
+    const StageSrc ss = stage_src(iter);
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const unsigned off = (unsigned)(((i * 4 + wave) * 64 + lane) * 8);
-      dma16(p.qt + tile * QT + off, QTs + buf * QT + (i * 4 + wave) * 512);
-      dma16(p.gt + tile * QT + off, GTs + buf * QT + (i * 4 + wave) * 512);
-    }
-    if (wave == 0) dma4(p.lse2p + tile * 64 + lane, lse_s + buf * BM);
-    if (wave == 1) dma4(p.dsp + tile * 64 + lane, dsum_s + buf * BM);
+    for (int i = 0; i < NQ + NI; ++i) dma_piece(ss, buf, i);
+    dma_rowvals(ss, buf);
   };
 
   int q_off[DK], t_off[4];
@@ -356,34 +409,59 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(DkvParams p) {
 
   auto iter_step = [&](int iter, auto buf_c) {
     constexpr int buf = decltype(buf_c)::value;
-    if (iter + 1 < n_iter) dma_stage(iter + 1, buf ^ 1);
+    const bool prefetch = iter + 1 < n_iter;
+    StageSrc nss{};
+    if (prefetch) {
+      nss = stage_src(iter + 1);
+      dma_rowvals(nss, buf ^ 1);
+    }
     const int qt = it.qt_first + iter % nqt;
     const __bf16* Qb = Qs + buf * QT;
     const __bf16* Gb = Gs + buf * QT;
     const __bf16* QTb = QTs + buf * QT;
     const __bf16* GTb = GTs + buf * QT;
+    const int i0 = qt * BM;  // first query (inside the segment) of this tile
 
-    // ---- S = Q K^T and dP = dO V^T : [64 queries] x [32 keys of this wave] ----
-    f32x16 s0, s1, p0, p1;
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      const bf16x8 aq0 = *reinterpret_cast<const bf16x8*>(Qb + q_off[ks]);
-      const bf16x8 aq1 = *reinterpret_cast<const bf16x8*>(Qb + q_off[ks] + 32 * D);
-      const bf16x8 ag0 = *reinterpret_cast<const bf16x8*>(Gb + q_off[ks]);
-      const bf16x8 ag1 = *reinterpret_cast<const bf16x8*>(Gb + q_off[ks] + 32 * D);
-      s0 = mfma32(aq0, kf[ks], ks == 0 ? zero16 : s0);
-      s1 = mfma32(aq1, kf[ks], ks == 0 ? zero16 : s1);
-      p0 = mfma32(ag0, vf[ks], ks == 0 ? zero16 : p0);
-      p1 = mfma32(ag1, vf[ks], ks == 0 ? zero16 : p1);
-    }
-
-    // ---- P = exp2(S c - LSE), dS = P (dP - D); entries a query does not see give P = dS = 0 ----
-    bf16x8 pfrag[4], dsfrag[4];  // B operands per k-step of 16 queries
-    const int i0 = qt * BM;      // first query (inside the segment) of this tile
+    // The 64 query rows are handled as two halves of 32; each half is a chain of stages separated by
+    // scheduling fences, every stage issuing the LDS reads of the next one together with its own MFMAs (and
+    // one piece of the next stage's global->LDS copies), so read latency hides behind matrix work.
+    constexpr int PIECES = NQ + NI;
+    int piece = 0;
+    auto next_piece = [&]() {
+      if (prefetch && piece < PIECES) dma_piece(nss, buf ^ 1, piece);
+      ++piece;
+    };
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      const f32x16& s = qb == 0 ? s0 : s1;
-      const f32x16& dp = qb == 0 ? p0 : p1;
+      auto ldq = [&](int ks) { return *reinterpret_cast<const bf16x8*>(Qb + q_off[ks] + qb * 32 * D); };
+      auto ldg = [&](int ks) { return *reinterpret_cast<const bf16x8*>(Gb + q_off[ks] + qb * 32 * D); };
+      // ---- S = Q K^T and dP = dO V^T : [32 queries] x [32 keys of this wave] ----
+      f32x16 s, dp;
+      bf16x8 aq[2][2], ag[2][2];
+      aq[0][0] = ldq(0); ag[0][0] = ldg(0); aq[0][1] = ldq(1); ag[0][1] = ldg(1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < DK / 2; ++g) {
+        const int cur = g & 1, nxt = cur ^ 1;
+        if (g + 1 < DK / 2) {
+          aq[nxt][0] = ldq(2 * g + 2); ag[nxt][0] = ldg(2 * g + 2);
+          aq[nxt][1] = ldq(2 * g + 3); ag[nxt][1] = ldg(2 * g + 3);
+        }
+        s = mfma32(aq[cur][0], kf[2 * g], g == 0 ? zero16 : s);
+        dp = mfma32(ag[cur][0], vf[2 * g], g == 0 ? zero16 : dp);
+        next_piece();
+        s = mfma32(aq[cur][1], kf[2 * g + 1], s);
+        dp = mfma32(ag[cur][1], vf[2 * g + 1], dp);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // operands of the first k-step of dV^T / dK^T, fetched while the exponentials are computed
+      bf16x8 tg[2][DB], tq[2][DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        tg[0][db] = *reinterpret_cast<const bf16x8*>(GTb + t_off[2 * qb] + db * 32 * BM);
+        tq[0][db] = *reinterpret_cast<const bf16x8*>(QTb + t_off[2 * qb] + db * 32 * BM);
+      }
+      // ---- P = exp2(S c - LSE), dS = P (dP - D); entries a query does not see give P = dS = 0 ----
       const bool need_mask = (i0 + 32 * qb) < (it.j0 + 32 * wave + 31 - it.ctx);
       float pv[16], dsv[16];
 #pragma unroll
@@ -402,25 +480,37 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(DkvParams p) {
           dsv[i] = pe * (dp[i] - d4[r]);
         }
       }
-      pfrag[2 * qb] = pack8(pv[0], pv[1], pv[2], pv[3], pv[4], pv[5], pv[6], pv[7]);
-      pfrag[2 * qb + 1] = pack8(pv[8], pv[9], pv[10], pv[11], pv[12], pv[13], pv[14], pv[15]);
-      dsfrag[2 * qb] = pack8(dsv[0], dsv[1], dsv[2], dsv[3], dsv[4], dsv[5], dsv[6], dsv[7]);
-      dsfrag[2 * qb + 1] = pack8(dsv[8], dsv[9], dsv[10], dsv[11], dsv[12], dsv[13], dsv[14], dsv[15]);
-    }
-
-    // ---- dV^T += dO^T P, dK^T += Q^T dS : [D] x [32 keys], contraction over the 64 queries ----
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
+      bf16x8 pfrag[2], dsfrag[2];  // B operands per k-step of 16 queries
+      pfrag[0] = pack8(pv[0], pv[1], pv[2], pv[3], pv[4], pv[5], pv[6], pv[7]);
+      pfrag[1] = pack8(pv[8], pv[9], pv[10], pv[11], pv[12], pv[13], pv[14], pv[15]);
+      dsfrag[0] = pack8(dsv[0], dsv[1], dsv[2], dsv[3], dsv[4], dsv[5], dsv[6], dsv[7]);
+      dsfrag[1] = pack8(dsv[8], dsv[9], dsv[10], dsv[11], dsv[12], dsv[13], dsv[14], dsv[15]);
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- dV^T += dO^T P, dK^T += Q^T dS : [D] x [32 keys], contraction over this half's 32 queries ----
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const bf16x8 ag = *reinterpret_cast<const bf16x8*>(GTb + t_off[ks] + db * 32 * BM);
-        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(QTb + t_off[ks] + db * 32 * BM);
-        dvacc[db] = mfma32(ag, pfrag[ks], dvacc[db]);
-        dkacc[db] = mfma32(aq, dsfrag[ks], dkacc[db]);
+        tg[1][db] = *reinterpret_cast<const bf16x8*>(GTb + t_off[2 * qb + 1] + db * 32 * BM);
+        tq[1][db] = *reinterpret_cast<const bf16x8*>(QTb + t_off[2 * qb + 1] + db * 32 * BM);
       }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dvacc[db] = mfma32(tg[0][db], pfrag[0], dvacc[db]);
+        dkacc[db] = mfma32(tq[0][db], dsfrag[0], dkacc[db]);
+        next_piece();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dvacc[db] = mfma32(tg[1][db], pfrag[1], dvacc[db]);
+        dkacc[db] = mfma32(tq[1][db], dsfrag[1], dkacc[db]);
+        next_piece();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    static_assert(2 * (DK / 2 + 2 * DB) >= PIECES, "not enough slots for the copies of one stage");
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    wg_barrier();
   };
 
   for (int iter = 0; iter < n_iter; iter += 2) {
@@ -513,7 +603,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.heads_per_wg = fwd_heads_per_wg(group); p.head_splits = group / p.heads_per_wg;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
-    const size_t smem = (size_t)6 * 32 * D * 2;
+    const size_t smem = (size_t)9 * 32 * D * 2;  // 3 stages of K, V and K^T tiles
     static bool attr = false;
     if ((e = set_smem(&bwd_dq_kernel<D>, smem, &attr)) != hipSuccess) return e;
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;

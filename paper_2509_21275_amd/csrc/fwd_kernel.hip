@@ -33,6 +33,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
   const int l32 = lane & 31, hh = lane >> 5;
+  stagger_wave_priority();
 
   const int inner_n = p.num_kv_heads * p.head_splits;
   const int inner = blockIdx.x % inner_n;

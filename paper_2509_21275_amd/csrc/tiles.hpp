@@ -81,6 +81,28 @@ __device__ __forceinline__ void dma_image(const __bf16* src, __bf16* lds_tile, i
   }
 }
 
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for every outstanding
+// global->LDS copy, including the ones prefetching later stages.  Callers wait (s_waitcnt vmcnt) for exactly
+// the copies the next stage needs before calling this; LDS reads of the finished stage have completed
+// because their values were consumed.
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Two waves that share a SIMD and run the same MFMA-phase / VALU-phase loop tend to fall into lockstep:
+// both want the matrix pipe at the same time, then both want the vector ALU, and the two pipes never
+// overlap.  Giving the waves of one SIMD different issue priorities (by the parity of their hardware
+// wave slot) breaks the symmetry: the favoured wave runs its phases back to back and the other one
+// fills the gaps, so matrix and vector work of different waves overlap.
+__device__ __forceinline__ void stagger_wave_priority() {
+  // HW_REG_HW_ID (register 4), bits [3:0] = wave slot on the SIMD
+  const unsigned slot = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 4);
+  if (slot & 1) __builtin_amdgcn_s_setprio(3);
+  else __builtin_amdgcn_s_setprio(0);
+}
+
 // 8 bf16 of (row, logical chunk c)
 template <int CHUNKS>
 __device__ __forceinline__ bf16x8 lds_chunk(const __bf16* tile, int row, int c) {
