@@ -16,7 +16,7 @@ def make_inputs(case, device="cuda"):
     return q, k, v, do
 
 
-def run_gpu(case, q, k, v, do, accumulate=False, dk_init=None, dv_init=None, scale=None, backward=True):
+def run_gpu(case, q, k, v, do=None, accumulate=False, dk_init=None, dv_init=None, scale=None, backward=True):
     import paper_2509_21275_amd as ca
     scale = case.scale if scale is None else scale
     desc = ca.make_desc(case.segs, case.num_q_heads, case.num_kv_heads, case.head_dim, case.total_q, case.total_kv,
