@@ -76,9 +76,9 @@ typedef struct {
 
 /*
  * Scratch sizes (bytes) for a descriptor: *fwd_bytes for chunk_attn_fwd, *bwd_bytes for
- * chunk_attn_bwd (the latter holds the float32 dQ accumulator, the row sums
- * D_i = <dO_i, O_i>, float32 dK/dV staging when accumulate_dkv is used, and the tile
- * schedule).  Either output pointer may be NULL.  Validates the descriptor.
+ * chunk_attn_bwd (the tile schedules, the row sums D_i = <dO_i, O_i>, and transposed
+ * tile images of the operands).  Either output pointer may be NULL.  Validates the
+ * descriptor.
  */
 int chunk_attn_workspace_bytes(const chunk_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
 
