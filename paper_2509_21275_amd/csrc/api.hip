@@ -2,6 +2,7 @@
 // schedule upload and kernel launches.  No device memory is allocated here; the only memory the
 // library owns is a small ring of pinned host buffers through which tile schedules are uploaded.
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -64,10 +65,12 @@ struct StagingRing {
 };
 StagingRing g_ring;
 
-// Forward workspace: [work items | transpose jobs] (uploaded as one blob) then the transposed V images.
+// Forward workspace: [work items | transpose jobs | redo flags (zero)] (uploaded as one blob) then the
+// transposed V images.
 struct FwdLayout {
   int tile_rows;
-  size_t items_bytes, jobs_off, blob_bytes, vt_off, total;
+  size_t items_bytes, jobs_off, flags_off, blob_bytes, vt_off, total;
+  int64_t blocks;
   int64_t kv_tiles;
   std::vector<FwdItem> items;
   std::vector<TileJob> jobs;
@@ -75,7 +78,7 @@ struct FwdLayout {
 
 void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_plan) {
   const int group = d->num_q_heads / d->num_kv_heads;
-  L.tile_rows = fwd_tile_rows(group);
+  L.tile_rows = tile_rows(group, fwd_waves(d->head_dim)) * fwd_qblocks(d->head_dim);
   size_t n_items = 0;
   if (with_plan) {
     L.items = plan_fwd(d, L.tile_rows);
@@ -87,7 +90,9 @@ void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_plan) {
   L.kv_tiles = count_tiles(d, true, 64);
   L.items_bytes = n_items * sizeof(FwdItem);
   L.jobs_off = align_up(L.items_bytes);
-  L.blob_bytes = L.jobs_off + (size_t)L.kv_tiles * sizeof(TileJob);
+  L.blocks = (int64_t)n_items * d->num_kv_heads * (group / heads_per_wg(group, fwd_waves(d->head_dim)));
+  L.flags_off = align_up(L.jobs_off + (size_t)L.kv_tiles * sizeof(TileJob));
+  L.blob_bytes = L.flags_off + (size_t)L.blocks * sizeof(int32_t);
   L.vt_off = align_up(L.blob_bytes);
   L.total = L.vt_off + align_up((size_t)L.kv_tiles * d->num_kv_heads * d->head_dim * 64 * sizeof(__bf16));
 }
@@ -161,7 +166,7 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   char* ws = static_cast<char*>(workspace);
 
-  std::vector<char> blob(L.blob_bytes);
+  std::vector<char> blob(L.blob_bytes, 0);
   std::memcpy(blob.data(), L.items.data(), L.items_bytes);
   std::memcpy(blob.data() + L.jobs_off, L.jobs.data(), L.jobs.size() * sizeof(TileJob));
   hipError_t e = g_ring.upload(ws, blob.data(), blob.size(), stream);
@@ -183,11 +188,15 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   p.num_q_heads = desc->num_q_heads;
   p.num_kv_heads = desc->num_kv_heads;
   p.group = desc->num_q_heads / desc->num_kv_heads;
-  p.heads_per_wg = fwd_heads_per_wg(p.group);
+  p.heads_per_wg = heads_per_wg(p.group, fwd_waves(desc->head_dim));
   p.head_splits = p.group / p.heads_per_wg;
   p.total_q = desc->total_q;
   p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
-  const int64_t blocks = (int64_t)L.items.size() * p.num_kv_heads * p.head_splits;
+  p.redo = desc->head_dim == 128 ? reinterpret_cast<int32_t*>(ws + L.flags_off) : nullptr;
+  // bf16 probabilities and fp32 sums hold 2^60 with room to spare; CHUNK_ATTN_FWD_REF_LIMIT overrides it (tests)
+  p.ref_limit = 60.0f;
+  if (const char* e = std::getenv("CHUNK_ATTN_FWD_REF_LIMIT")) p.ref_limit = (float)std::atof(e);
+  const int64_t blocks = L.blocks;
   if (blocks > 0x7fffffff) return CHUNK_ATTN_UNSUPPORTED;
   ProfileEvents pe = profile_events();
   profile_events() = ProfileEvents{};

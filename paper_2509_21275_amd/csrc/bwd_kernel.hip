@@ -18,6 +18,7 @@
 // P is recomputed from the saved log-sum-exp in both kernels.  All operands reach LDS by global->LDS
 // copies and are read with 16-byte LDS reads from swizzled tiles (tiles.hpp).
 #include <cstring>
+#include <cstdlib>
 #include <type_traits>
 
 #include "kernels.hpp"
@@ -287,39 +288,59 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
 
 // ------------------------------------------------------------------------------------------------
 // bwd_dkv
+//
+// One workgroup = 128 consecutive keys of one segment and one key/value head, 8 waves.  The four
+// contractions of a (32-query, 32-key) block are split between two waves that share the block's keys:
+//   wave A (waves 0..3): S = Q K^T, P = exp2(S c - LSE), dV^T += dO^T P;  hands P (bf16) to wave B through LDS
+//   wave B (waves 4..7): dP = dO V^T, dS = P (dP - D),   dK^T += Q^T dS;  runs one step behind wave A
+// so each wave keeps one fragment set (K or V) and one accumulator (dV^T or dK^T) and the whole kernel
+// fits 256 registers per lane: two waves per SIMD, whose matrix and vector phases overlap.
+// The workgroup walks the group's query heads and, per head, the 32-row query tiles that see its keys.
+// Operand tiles of a step (Q and dO rows, Q^T and dO^T images) sit in a 4-slot LDS ring filled two steps
+// ahead by global->LDS copies; the tiles wave B reads one step late (Q^T, D) are placed one slot later
+// than the others, so that everything read in step g sits in "slot g % 4".
 // ------------------------------------------------------------------------------------------------
 struct DkvParams {
   const __bf16 *q, *k, *v, *d_o;
-  const __bf16* qt;     // transposed Q images  [Hq][total_q_tiles][D][64]
-  const __bf16* gt;     // transposed dO images [Hq][total_q_tiles][D][64]
+  const __bf16* qt;     // transposed Q images  [Hq][total_q32_tiles][D][32]
+  const __bf16* gt;     // transposed dO images [Hq][total_q32_tiles][D][32]
   const float* lse2p;   // [Hq][total_q_tiles * 64]
   const float* dsp;
   __bf16 *dk, *dv;
   const DkvItem* items;
-  int64_t total_q_tiles;
+  int64_t total_q_tiles, total_q32_tiles;
   int32_t num_q_heads, num_kv_heads, group;
   float scale, scale_log2;
   int32_t accumulate;
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void bwd_dkv_kernel(DkvParams p) {
-  constexpr int BM = 64;       // query rows per LDS tile
-  constexpr int KC = D / 8;
-  constexpr int DK = D / 16;
-  constexpr int DB = D / 32;
-  constexpr int QT = BM * D;   // elements per tile / image
+__global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
+  constexpr int BM = 32;       // query rows per step
+  constexpr int KC = D / 8;    // 16-byte chunks per operand row
+  constexpr int DK = D / 16;   // k-steps over the head dimension
+  constexpr int DB = D / 32;   // 32-row blocks of dK^T / dV^T
+  constexpr int QT = BM * D;   // elements per operand tile
+  constexpr int NS = 4;        // ring slots
+  constexpr int PT = 4 * 64 * 16;      // elements of one P hand-over slot: 4 key blocks x 64 lanes x 16 values
+  constexpr int CH = BM * KC;          // 16-byte chunks per operand tile
+  constexpr int PER = 4 * CH / 512;    // global->LDS copies per thread and stage
+  constexpr int RV = 64;               // floats per slot of the LSE / D rows (32 used; a whole wave copies them)
+  static_assert(PER == 4 || PER == 2, "head_dim 128 or 64");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  __bf16* Qs = reinterpret_cast<__bf16*>(smem);  // [2][BM][D]  rows
-  __bf16* Gs = Qs + 2 * QT;                      // [2][BM][D]  rows (dO)
-  __bf16* QTs = Gs + 2 * QT;                     // [2][D][BM]  image
-  __bf16* GTs = QTs + 2 * QT;                    // [2][D][BM]  image
-  float* lse_s = reinterpret_cast<float*>(GTs + 2 * QT);  // [2][BM]
-  float* dsum_s = lse_s + 2 * BM;                          // [2][BM]
+  lds_bf16* const L = (lds_bf16*)smem;
+  constexpr int Q_OFF = 0;                 // [NS][BM][D]  Q rows        (wave A, step g)
+  constexpr int G_OFF = Q_OFF + NS * QT;   // [NS][BM][D]  dO rows       (wave B, step g)
+  constexpr int QT_OFF = G_OFF + NS * QT;  // [NS][D][BM]  Q^T image     (wave B, step g + 1)
+  constexpr int GT_OFF = QT_OFF + NS * QT; // [NS][D][BM]  dO^T image    (wave A, step g)
+  constexpr int P_OFF = GT_OFF + NS * QT;  // [2][PT]      P hand-over
+  lds_f32* const lse_s = (lds_f32*)(L + P_OFF + 2 * PT);  // [NS][RV]  (wave A, step g)
+  lds_f32* const dsum_s = lse_s + NS * RV;                // [NS][RV]  (wave B, step g + 1)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int role = wave >> 2, kb = wave & 3;
   const int l32 = lane & 31, hh = lane >> 5;
 
   const int kvh = blockIdx.x % p.num_kv_heads;
@@ -328,218 +349,221 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(DkvParams p) {
   const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
   const float c = p.scale_log2;
 
-  // this wave's K / V fragments (B operands): lane holds X[key = 32 wave + l32][16 ks + 8 hh ..+7]
-  bf16x8 kf[DK], vf[DK];
+  // this wave's K (wave A) or V (wave B) fragments, B operands: lane holds X[key = 32 kb + l32][16 ks + 8 hh ..+7]
+  bf16x8 bfrag[DK];
   {
-    const int64_t grow = it.kv_row0 + min(32 * wave + l32, it.kv_rows - 1);
+    const __bf16* src = role ? p.v : p.k;
+    const int64_t grow = it.kv_row0 + min(32 * kb + l32, it.kv_rows - 1);
     const int64_t off = grow * kv_stride + (int64_t)kvh * D + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      kf[ks] = *reinterpret_cast<const bf16x8*>(p.k + off + 16 * ks);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(p.v + off + 16 * ks);
-    }
+    for (int ks = 0; ks < DK; ++ks) bfrag[ks] = *reinterpret_cast<const bf16x8*>(src + off + 16 * ks);
   }
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  f32x16 dkacc[DB], dvacc[DB];  // dK^T, dV^T: [D] x [32 keys of this wave]
+  f32x16 acc[DB];  // dV^T (wave A) or dK^T (wave B): [D] x [32 keys of this wave]
 #pragma unroll
-  for (int db = 0; db < DB; ++db) { dkacc[db] = zero16; dvacc[db] = zero16; }
+  for (int db = 0; db < DB; ++db) acc[db] = zero16;
 
   const int nqt = it.n_qt - it.qt_first;
-  const int n_iter = nqt * G;
+  const int n_iter = nqt * G;  // stages: (head in group, query tile), head-major
 
-  // ---- staging of one (head, query tile): Q, dO rows; Q^T, dO^T images; LSE, D ----
-  constexpr int NQ = BM * KC / 256, NI = QT / 8 / 256;
-  unsigned q_src[NQ];
-  int q_row[NQ];
+  // ---- staging: each thread copies PER 16-byte chunks per stage, one of each operand tile (two of four for d = 64);
+  // wave 0 also copies the stage's LSE rows and wave 1 its D rows.  No per-lane branches. ----
+  const int x0 = (PER == 4 ? wave : (wave & 3)) * 64;  // wave-uniform first chunk inside the tile
+  const int r_row = (x0 + lane) / KC;
+  const int r_chunk = unswz<KC>(r_row, (x0 + lane) % KC) * 8;
+  int d_qt = it.qt_first, d_hg = 0;  // (query tile, head in group) of the next stage to copy
+  auto dma_stage = [&](auto aslot_c) {
+    constexpr int as = decltype(aslot_c)::value, bs = (as + 1) % NS;
+    const int head = kvh * G + d_hg;
+    const int last_row = it.q_len - 1 - d_qt * BM;  // >= 0; rows past it repeat it (their P is 0)
+    const int64_t roff = (int64_t)(it.q_row_seg + d_qt * BM) * q_stride + (int64_t)head * D;
+    const int64_t img = ((int64_t)head * p.total_q32_tiles + it.q_img0 + d_qt) * QT;
+    const int64_t slot = ((int64_t)head * p.total_q_tiles + it.q_tile0) * 64 + d_qt * BM;
+    if (wave == 0) dma4(p.lse2p + slot + lane, lse_s + as * RV);
+    if (wave == 1) dma4(p.dsp + slot + lane, dsum_s + bs * RV);
+    const unsigned row_off = (unsigned)(min(r_row, last_row) * (int)q_stride + r_chunk);
+    const unsigned img_off = (unsigned)((x0 + lane) * 8);
 #pragma unroll
-  for (int i = 0; i < NQ; ++i) {
-    const int x = (i * 4 + wave) * 64 + lane;
-    q_row[i] = x / KC;
-    q_src[i] = (unsigned)(q_row[i] * (int)q_stride + unswz<KC>(q_row[i], x % KC) * 8);
-  }
-  // The copies of one (head, query tile) stage are split into NQ + NI pieces per lane (piece i < NQ: a Q and a dO
-  // row chunk; else a Q^T and a dO^T image chunk), so that they can be issued between MFMAs.
-  struct StageSrc { int64_t roff, tile; int last_row; };
-  auto stage_src = [&](int iter) {
-    const int hg = iter / nqt, qt = it.qt_first + iter % nqt;
-    const int head = kvh * G + hg;
-    StageSrc ss;
-    ss.last_row = it.q_len - 1 - qt * BM;  // >= 0
-    ss.roff = (int64_t)(it.q_row_seg + qt * BM) * q_stride + (int64_t)head * D;  // wave-uniform
-    ss.tile = (int64_t)head * p.total_q_tiles + it.q_tile0 + qt;                  // wave-uniform
-    return ss;
-  };
-  auto dma_piece = [&](const StageSrc& ss, int buf, int i) {
-    if (i < NQ) {
-      unsigned off = q_src[i];
-      if (ss.last_row < BM - 1) off -= (unsigned)((q_row[i] - min(q_row[i], ss.last_row)) * (int)q_stride);
-      dma16(p.q + ss.roff + off, Qs + buf * QT + (i * 4 + wave) * 512);
-      dma16(p.d_o + ss.roff + off, Gs + buf * QT + (i * 4 + wave) * 512);
-    } else {
-      const int j = i - NQ;
-      const unsigned off = (unsigned)(((j * 4 + wave) * 64 + lane) * 8);
-      dma16(p.qt + ss.tile * QT + off, QTs + buf * QT + (j * 4 + wave) * 512);
-      dma16(p.gt + ss.tile * QT + off, GTs + buf * QT + (j * 4 + wave) * 512);
+    for (int i = 0; i < PER; ++i) {
+      const int tile = PER == 4 ? i : 2 * i + (wave >> 2);  // 0: Q rows, 1: dO rows, 2: Q^T image, 3: dO^T image
+      if (tile == 0) dma16(p.q + roff + row_off, L + Q_OFF + as * QT + x0 * 8);
+      else if (tile == 1) dma16(p.d_o + roff + row_off, L + G_OFF + as * QT + x0 * 8);
+      else if (tile == 2) dma16(p.qt + img + img_off, L + QT_OFF + bs * QT + x0 * 8);
+      else dma16(p.gt + img + img_off, L + GT_OFF + as * QT + x0 * 8);
     }
-  };
-  auto dma_rowvals = [&](const StageSrc& ss, int buf) {
-    if (wave == 0) dma4(p.lse2p + ss.tile * 64 + lane, lse_s + buf * BM);
-    if (wave == 1) dma4(p.dsp + ss.tile * 64 + lane, dsum_s + buf * BM);
-  };
-  auto dma_stage = [&](int iter, int buf) {
-    const StageSrc ss = stage_src(iter);
-#pragma unroll
-    for (int i = 0; i < NQ + NI; ++i) dma_piece(ss, buf, i);
-    dma_rowvals(ss, buf);
+    if (++d_qt == it.n_qt) { d_qt = it.qt_first; ++d_hg; }
   };
 
-  int q_off[DK], t_off[4];
-#pragma unroll
-  for (int ks = 0; ks < DK; ++ks) q_off[ks] = tile_elem<KC>(l32, 2 * ks + hh);
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) t_off[ks] = tile_elem<8>(l32, 2 * ks + hh);
+  // key index of this lane's column relative to the context: query i of the segment sees it iff i >= jrel
+  const int jrel = it.j0 + 32 * kb + l32 - it.ctx;
+  const int jrel_lo = it.j0 + 32 * kb - it.ctx;  // of the wave's first key
 
-  // key index of this lane's column inside the segment, relative to the context: query i sees it iff i >= jrel
-  const int jrel = it.j0 + 32 * wave + l32 - it.ctx;
-
-  if (n_iter > 0) dma_stage(0, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-
-  auto iter_step = [&](int iter, auto buf_c) {
-    constexpr int buf = decltype(buf_c)::value;
-    const bool prefetch = iter + 1 < n_iter;
-    StageSrc nss{};
-    if (prefetch) {
-      nss = stage_src(iter + 1);
-      dma_rowvals(nss, buf ^ 1);
-    }
-    const int qt = it.qt_first + iter % nqt;
-    const __bf16* Qb = Qs + buf * QT;
-    const __bf16* Gb = Gs + buf * QT;
-    const __bf16* QTb = QTs + buf * QT;
-    const __bf16* GTb = GTs + buf * QT;
-    const int i0 = qt * BM;  // first query (inside the segment) of this tile
-
-    // The 64 query rows are handled as two halves of 32; each half is a chain of stages separated by
-    // scheduling fences, every stage issuing the LDS reads of the next one together with its own MFMAs (and
-    // one piece of the next stage's global->LDS copies), so read latency hides behind matrix work.
-    constexpr int PIECES = NQ + NI;
-    int piece = 0;
-    auto next_piece = [&]() {
-      if (prefetch && piece < PIECES) dma_piece(nss, buf ^ 1, piece);
-      ++piece;
-    };
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      auto ldq = [&](int ks) { return *reinterpret_cast<const bf16x8*>(Qb + q_off[ks] + qb * 32 * D); };
-      auto ldg = [&](int ks) { return *reinterpret_cast<const bf16x8*>(Gb + q_off[ks] + qb * 32 * D); };
-      // ---- S = Q K^T and dP = dO V^T : [32 queries] x [32 keys of this wave] ----
-      f32x16 s, dp;
-      bf16x8 aq[2][2], ag[2][2];
-      aq[0][0] = ldq(0); ag[0][0] = ldg(0); aq[0][1] = ldq(1); ag[0][1] = ldg(1);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int g = 0; g < DK / 2; ++g) {
-        const int cur = g & 1, nxt = cur ^ 1;
-        if (g + 1 < DK / 2) {
-          aq[nxt][0] = ldq(2 * g + 2); ag[nxt][0] = ldg(2 * g + 2);
-          aq[nxt][1] = ldq(2 * g + 3); ag[nxt][1] = ldg(2 * g + 3);
-        }
-        s = mfma32(aq[cur][0], kf[2 * g], g == 0 ? zero16 : s);
-        dp = mfma32(ag[cur][0], vf[2 * g], g == 0 ? zero16 : dp);
-        next_piece();
-        s = mfma32(aq[cur][1], kf[2 * g + 1], s);
-        dp = mfma32(ag[cur][1], vf[2 * g + 1], dp);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // operands of the first k-step of dV^T / dK^T, fetched while the exponentials are computed
-      bf16x8 tg[2][DB], tq[2][DB];
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        tg[0][db] = *reinterpret_cast<const bf16x8*>(GTb + t_off[2 * qb] + db * 32 * BM);
-        tq[0][db] = *reinterpret_cast<const bf16x8*>(QTb + t_off[2 * qb] + db * 32 * BM);
-      }
-      // ---- P = exp2(S c - LSE), dS = P (dP - D); entries a query does not see give P = dS = 0 ----
-      const bool need_mask = (i0 + 32 * qb) < (it.j0 + 32 * wave + 31 - it.ctx);
-      float pv[16], dsv[16];
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + buf * BM + 32 * qb + 8 * g + 4 * hh);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dsum_s + buf * BM + 32 * qb + 8 * g + 4 * hh);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int i = 4 * g + r;
-          float pe = __builtin_amdgcn_exp2f(s[i] * c - l4[r]);
-          if (need_mask) {
-            const int qi = i0 + 32 * qb + 8 * g + 4 * hh + r;
-            if (qi < jrel) pe = 0.f;
-          }
-          pv[i] = pe;
-          dsv[i] = pe * (dp[i] - d4[r]);
-        }
-      }
-      bf16x8 pfrag[2], dsfrag[2];  // B operands per k-step of 16 queries
-      pfrag[0] = pack8(pv[0], pv[1], pv[2], pv[3], pv[4], pv[5], pv[6], pv[7]);
-      pfrag[1] = pack8(pv[8], pv[9], pv[10], pv[11], pv[12], pv[13], pv[14], pv[15]);
-      dsfrag[0] = pack8(dsv[0], dsv[1], dsv[2], dsv[3], dsv[4], dsv[5], dsv[6], dsv[7]);
-      dsfrag[1] = pack8(dsv[8], dsv[9], dsv[10], dsv[11], dsv[12], dsv[13], dsv[14], dsv[15]);
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- dV^T += dO^T P, dK^T += Q^T dS : [D] x [32 keys], contraction over this half's 32 queries ----
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        tg[1][db] = *reinterpret_cast<const bf16x8*>(GTb + t_off[2 * qb + 1] + db * 32 * BM);
-        tq[1][db] = *reinterpret_cast<const bf16x8*>(QTb + t_off[2 * qb + 1] + db * 32 * BM);
-      }
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        dvacc[db] = mfma32(tg[0][db], pfrag[0], dvacc[db]);
-        dkacc[db] = mfma32(tq[0][db], dsfrag[0], dkacc[db]);
-        next_piece();
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        dvacc[db] = mfma32(tg[1][db], pfrag[1], dvacc[db]);
-        dkacc[db] = mfma32(tq[1][db], dsfrag[1], dkacc[db]);
-        next_piece();
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    static_assert(2 * (DK / 2 + 2 * DB) >= PIECES, "not enough slots for the copies of one stage");
-
+  // prologue: stages 0 and 1 (after the fragment loads, so that the waits below count only copies)
+  dma_stage(std::integral_constant<int, 0>{});
+  if (n_iter > 1) {
+    dma_stage(std::integral_constant<int, 1>{});
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER) : "memory");
+  } else {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  wg_barrier();
+
+  int c_qt = it.qt_first, p_qt = it.qt_first;  // query tile of stage g and of stage g - 1
+  // end of step g: stage g + 1 must have landed and wave A's P must be visible; the copies issued in this
+  // step (stage g + 2) may still be in flight
+  auto end_step = [&](bool more) {
+    p_qt = c_qt;
+    if (++c_qt == it.n_qt) c_qt = it.qt_first;
+    if (more) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(PER) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     wg_barrier();
   };
 
-  for (int iter = 0; iter < n_iter; iter += 2) {
-    iter_step(iter, std::integral_constant<int, 0>{});
-    if (iter + 1 < n_iter) iter_step(iter + 1, std::integral_constant<int, 1>{});
+  if (role == 0) {
+    // ================= wave A: S = Q K^T, P, dV^T += dO^T P =================
+    int x_off[DK], t_off[2];
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) x_off[ks] = Q_OFF + tile_elem<KC>(l32, 2 * ks + hh);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) t_off[ks] = GT_OFF + tile_elem<4>(l32, 2 * ks + hh);
+    const lds_f32* const rv = lse_s + 4 * hh;
+    lds_bf16* const pex = L + P_OFF + kb * 1024 + lane * 8;
+
+    auto step = [&](int g, auto u_c) {
+      constexpr int u = decltype(u_c)::value;
+      const bool more = g + 2 < n_iter;
+      const int i0 = c_qt * BM;  // first query (inside the segment) of block g
+      if (g < n_iter && i0 + BM - 1 >= jrel_lo) {  // else: no block, or nothing of it visible to this wave's keys
+        bf16x8 a[DK], t[2][DB];
+        f32x4 r4[4];  // LSE of rows 8 g4 + 4 hh + 0..3
+#pragma unroll
+        for (int ks = 0; ks < DK; ++ks) a[ks] = lds_load8(L + x_off[ks] + u * QT);
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) r4[g4] = lds_load4f(rv + u * RV + 8 * g4);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int db = 0; db < DB; ++db) t[ks][db] = lds_load8(L + t_off[ks] + u * QT + db * 32 * BM);
+        f32x16 s;
+#pragma unroll
+        for (int ks = 0; ks < DK; ++ks) s = mfma32(a[ks], bfrag[ks], ks == 0 ? zero16 : s);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) dma_stage(std::integral_constant<int, (u + 2) % NS>{});
+        __builtin_amdgcn_sched_barrier(0);
+        // P = exp2(S c - LSE); entries a query does not see give P = 0
+        float w[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) w[i] = __builtin_amdgcn_exp2f(s[i] * c - r4[i >> 2][i & 3]);
+        if (i0 < jrel_lo + 31) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int qi = i0 + 8 * (i >> 2) + 4 * hh + (i & 3);
+            if (qi < jrel) w[i] = 0.f;
+          }
+        }
+        const bf16x8 f0 = pack8(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]);
+        const bf16x8 f1 = pack8(w[8], w[9], w[10], w[11], w[12], w[13], w[14], w[15]);
+        lds_store8(pex + (u & 1) * PT, f0);
+        lds_store8(pex + (u & 1) * PT + 512, f1);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma32(t[0][db], f0, acc[db]);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma32(t[1][db], f1, acc[db]);
+      } else if (more) {
+        dma_stage(std::integral_constant<int, (u + 2) % NS>{});
+      }
+      end_step(more);
+    };
+    for (int g = 0; g <= n_iter; g += NS) {
+      step(g, std::integral_constant<int, 0>{});
+      if (g + 1 <= n_iter) step(g + 1, std::integral_constant<int, 1>{});
+      if (g + 2 <= n_iter) step(g + 2, std::integral_constant<int, 2>{});
+      if (g + 3 <= n_iter) step(g + 3, std::integral_constant<int, 3>{});
+    }
+  } else {
+    // ================= wave B: dP = dO V^T, dS = P (dP - D), dK^T += Q^T dS =================
+    // In step g it first finishes block g - 1 (vector work with wave A's P, then dK^T) and then starts block g
+    // (dP): right after the barrier one wave of each SIMD begins with matrix work and the other with vector work.
+    int x_off[DK], t_off[2];
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) x_off[ks] = G_OFF + tile_elem<KC>(l32, 2 * ks + hh);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) t_off[ks] = QT_OFF + tile_elem<4>(l32, 2 * ks + hh);
+    const lds_f32* const rv = dsum_s + 4 * hh;
+    const lds_bf16* const pex = L + P_OFF + kb * 1024 + lane * 8;
+    f32x16 dp = zero16;  // dP of the block whose dS is formed in the next step
+
+    auto step = [&](int g, auto u_c) {
+      constexpr int u = decltype(u_c)::value;
+      const bool more = g + 2 < n_iter;
+      const bool cur_vis = g < n_iter && (c_qt * BM + BM - 1 >= jrel_lo);
+      const bool prev_vis = g >= 1 && (p_qt * BM + BM - 1 >= jrel_lo);
+      bf16x8 a[DK];
+      if (cur_vis) {
+#pragma unroll
+        for (int ks = 0; ks < DK; ++ks) a[ks] = lds_load8(L + x_off[ks] + u * QT);
+      }
+      if (prev_vis) {
+        const bf16x8 p0 = lds_load8(pex + ((u & 1) ^ 1) * PT);
+        const bf16x8 p1 = lds_load8(pex + ((u & 1) ^ 1) * PT + 512);
+        f32x4 r4[4];  // D of rows 8 g4 + 4 hh + 0..3
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) r4[g4] = lds_load4f(rv + u * RV + 8 * g4);
+        bf16x8 t[2][DB];  // Q^T operands
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int db = 0; db < DB; ++db) t[ks][db] = lds_load8(L + t_off[ks] + u * QT + db * 32 * BM);
+        float w[16];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          w[i] = (float)p0[i] * (dp[i] - r4[i >> 2][i & 3]);
+          w[8 + i] = (float)p1[i] * (dp[8 + i] - r4[2 + (i >> 2)][i & 3]);
+        }
+        const bf16x8 f0 = pack8(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]);
+        const bf16x8 f1 = pack8(w[8], w[9], w[10], w[11], w[12], w[13], w[14], w[15]);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma32(t[0][db], f0, acc[db]);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma32(t[1][db], f1, acc[db]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) dma_stage(std::integral_constant<int, (u + 2) % NS>{});
+      __builtin_amdgcn_sched_barrier(0);
+      if (cur_vis) {
+#pragma unroll
+        for (int ks = 0; ks < DK; ++ks) dp = mfma32(a[ks], bfrag[ks], ks == 0 ? zero16 : dp);
+      }
+      end_step(more);
+    };
+    for (int g = 0; g <= n_iter; g += NS) {
+      step(g, std::integral_constant<int, 0>{});
+      if (g + 1 <= n_iter) step(g + 1, std::integral_constant<int, 1>{});
+      if (g + 2 <= n_iter) step(g + 2, std::integral_constant<int, 2>{});
+      if (g + 3 <= n_iter) step(g + 3, std::integral_constant<int, 3>{});
+    }
   }
 
-  // ---- epilogue: dK = scale * dK^T, dV = dV^T, written (or added) as bf16 ----
+  // ---- epilogue: dV = dV^T (wave A), dK = scale * dK^T (wave B), written (or added) as bf16 ----
   {
-    const int kr = 32 * wave + l32;
+    const int kr = 32 * kb + l32;
     if (kr < it.kv_rows) {
       const int64_t off = ((int64_t)it.kv_row0 + kr) * kv_stride + (int64_t)kvh * D;
+      __bf16* const out = role ? p.dk : p.dv;
+      const float f = role ? p.scale : 1.0f;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int col = 32 * db + 8 * g + 4 * hh;
-          float k0 = dkacc[db][4 * g] * p.scale, k1 = dkacc[db][4 * g + 1] * p.scale,
-                k2 = dkacc[db][4 * g + 2] * p.scale, k3 = dkacc[db][4 * g + 3] * p.scale;
-          float v0 = dvacc[db][4 * g], v1 = dvacc[db][4 * g + 1], v2 = dvacc[db][4 * g + 2], v3 = dvacc[db][4 * g + 3];
-          bf16x4* dkp = reinterpret_cast<bf16x4*>(p.dk + off + col);
-          bf16x4* dvp = reinterpret_cast<bf16x4*>(p.dv + off + col);
+          float v0 = acc[db][4 * g] * f, v1 = acc[db][4 * g + 1] * f, v2 = acc[db][4 * g + 2] * f,
+                v3 = acc[db][4 * g + 3] * f;
+          bf16x4* op = reinterpret_cast<bf16x4*>(out + off + 32 * db + 8 * g + 4 * hh);
           if (p.accumulate) {
-            const bf16x4 ok = *dkp, ov = *dvp;
-            k0 += (float)ok[0]; k1 += (float)ok[1]; k2 += (float)ok[2]; k3 += (float)ok[3];
-            v0 += (float)ov[0]; v1 += (float)ov[1]; v2 += (float)ov[2]; v3 += (float)ov[3];
+            const bf16x4 old = *op;
+            v0 += (float)old[0]; v1 += (float)old[1]; v2 += (float)old[2]; v3 += (float)old[3];
           }
-          *dkp = pack4(k0, k1, k2, k3);
-          *dvp = pack4(v0, v1, v2, v3);
+          *op = pack4(v0, v1, v2, v3);
         }
     }
   }
@@ -564,6 +588,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
   char* ws = a.workspace;
   const TileJob* qjobs = reinterpret_cast<const TileJob*>(ws + P.qjobs_off);
   const TileJob* kjobs = reinterpret_cast<const TileJob*>(ws + P.kjobs_off);
+  const TileJob* qjobs32 = reinterpret_cast<const TileJob*>(ws + P.qjobs32_off);
   float* lse2p = reinterpret_cast<float*>(ws + P.lse2p_off);
   float* dsp = reinterpret_cast<float*>(ws + P.dsp_off);
   __bf16* qt = reinterpret_cast<__bf16*>(ws + P.qt_off);
@@ -579,8 +604,8 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
                        P.q_tiles, d->total_q, d->num_q_heads, lse2p, dsp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  if ((e = launch_transpose(a.q, d->num_q_heads, D, 64, qjobs, (int)P.qjobs.size(), P.q_tiles, qt, stream)) != hipSuccess) return e;
-  if ((e = launch_transpose(a.d_o, d->num_q_heads, D, 64, qjobs, (int)P.qjobs.size(), P.q_tiles, gt, stream)) != hipSuccess) return e;
+  if ((e = launch_transpose(a.q, d->num_q_heads, D, 32, qjobs32, (int)P.qjobs32.size(), P.q32_tiles, qt, stream)) != hipSuccess) return e;
+  if ((e = launch_transpose(a.d_o, d->num_q_heads, D, 32, qjobs32, (int)P.qjobs32.size(), P.q32_tiles, gt, stream)) != hipSuccess) return e;
   if ((e = launch_transpose(a.k, d->num_kv_heads, D, 32, kjobs, (int)P.kjobs.size(), P.kv32_tiles, kt, stream)) != hipSuccess) return e;
 
   if (!a.accumulate) {  // rows no segment covers receive no gradient
@@ -601,7 +626,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.items = reinterpret_cast<const DqItem*>(ws + P.dq_items_off);
     p.total_kv32_tiles = P.kv32_tiles; p.total_q_tiles = P.q_tiles;
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
-    p.heads_per_wg = fwd_heads_per_wg(group); p.head_splits = group / p.heads_per_wg;
+    p.heads_per_wg = heads_per_wg(group, dq_waves(D)); p.head_splits = group / p.heads_per_wg;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     const size_t smem = (size_t)9 * 32 * D * 2;  // 3 stages of K, V and K^T tiles
     static bool attr = false;
@@ -616,11 +641,12 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.qt = qt; p.gt = gt; p.lse2p = lse2p; p.dsp = dsp;
     p.dk = a.dk; p.dv = a.dv;
     p.items = reinterpret_cast<const DkvItem*>(ws + P.dkv_items_off);
-    p.total_q_tiles = P.q_tiles;
+    p.total_q_tiles = P.q_tiles; p.total_q32_tiles = P.q32_tiles;
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
-    const size_t smem = (size_t)8 * 64 * D * 2 + 4 * 64 * sizeof(float);
+    // 4 ring slots of four 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
+    const size_t smem = (size_t)16 * 32 * D * 2 + 2 * 4096 * 2 + 2 * 4 * 64 * sizeof(float);
     static bool attr = false;
     if ((e = set_smem(&bwd_dkv_kernel<D>, smem, &attr)) != hipSuccess) return e;
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
@@ -628,7 +654,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     ProfileEvents pe = profile_events();
     profile_events() = ProfileEvents{};
     if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dkv_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((bwd_dkv_kernel<D>), dim3((unsigned)blocks), dim3(512), smem, stream, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return e;
   }
@@ -639,15 +665,17 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
 
 void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   const int group = d->num_q_heads / d->num_kv_heads;
-  const int dq_rows = fwd_tile_rows(group);
+  const int dq_rows = tile_rows(group, dq_waves(d->head_dim));
   P.q_tiles = count_tiles(d, false, 64);
   P.kv32_tiles = count_tiles(d, true, 32);
+  P.q32_tiles = count_tiles(d, false, 32);
   size_t n_dq = 0, n_dkv = 0;
   if (with_plan) {
     P.dq_items = plan_dq(d, dq_rows);
     P.dkv_items = plan_dkv(d);
     P.qjobs = tile_jobs(d, false, 64, nullptr);
     P.kjobs = tile_jobs(d, true, 32, nullptr);
+    P.qjobs32 = tile_jobs(d, false, 32, nullptr);
     n_dq = P.dq_items.size();
     n_dkv = P.dkv_items.size();
   } else {
@@ -660,12 +688,13 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   P.dkv_items_off = up256(n_dq * sizeof(DqItem));
   P.qjobs_off = P.dkv_items_off + up256(n_dkv * sizeof(DkvItem));
   P.kjobs_off = P.qjobs_off + up256((size_t)P.q_tiles * sizeof(TileJob));
-  P.blob_bytes = P.kjobs_off + up256((size_t)P.kv32_tiles * sizeof(TileJob));
+  P.qjobs32_off = P.kjobs_off + up256((size_t)P.kv32_tiles * sizeof(TileJob));
+  P.blob_bytes = P.qjobs32_off + up256((size_t)P.q32_tiles * sizeof(TileJob));
   const size_t row_slots = (size_t)d->num_q_heads * P.q_tiles * 64;
   P.lse2p_off = P.blob_bytes;
   P.dsp_off = P.lse2p_off + up256(row_slots * sizeof(float));
   P.qt_off = P.dsp_off + up256(row_slots * sizeof(float));
-  const size_t qimg = up256(row_slots * d->head_dim * sizeof(__bf16));
+  const size_t qimg = up256((size_t)d->num_q_heads * P.q32_tiles * 32 * d->head_dim * sizeof(__bf16));
   P.gt_off = P.qt_off + qimg;
   P.kt_off = P.gt_off + qimg;
   P.total = P.kt_off + up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16));
@@ -677,6 +706,7 @@ std::vector<char> bwd_blob(const BwdPlan& P) {
   std::memcpy(blob.data() + P.dkv_items_off, P.dkv_items.data(), P.dkv_items.size() * sizeof(DkvItem));
   std::memcpy(blob.data() + P.qjobs_off, P.qjobs.data(), P.qjobs.size() * sizeof(TileJob));
   std::memcpy(blob.data() + P.kjobs_off, P.kjobs.data(), P.kjobs.size() * sizeof(TileJob));
+  std::memcpy(blob.data() + P.qjobs32_off, P.qjobs32.data(), P.qjobs32.size() * sizeof(TileJob));
   return blob;
 }
 

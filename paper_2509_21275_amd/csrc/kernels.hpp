@@ -17,15 +17,26 @@ struct FwdParams {
   const FwdItem* items;
   int64_t total_kv_tiles;
   int32_t num_q_heads, num_kv_heads, group;  // group = Hq / Hkv
-  int32_t heads_per_wg;                      // query heads of one group handled by one workgroup (1, 2 or 4)
+  int32_t heads_per_wg;                      // query heads of one group handled by one workgroup (a power of two)
   int32_t head_splits;                       // group / heads_per_wg
   int32_t total_q;
   float scale_log2;                          // softmax scale * log2(e)
+  int32_t* redo;                             // per-workgroup redo flags of the pipelined forward (null: run every item)
+  float ref_limit;                           // log2 growth of the row maximum past the first tile's that raises the flag
 };
 
 // rows of query tile per forward work item for a given head layout
-inline int fwd_heads_per_wg(int group) { return group % 4 == 0 ? 4 : (group % 2 == 0 ? 2 : 1); }
-inline int fwd_tile_rows(int group) { return 32 * (4 / fwd_heads_per_wg(group)); }
+// Shape of a query-stationary workgroup (forward and dQ kernels): `waves` waves of 32 query rows each, spread
+// over as many query heads of one group as divide both (so that the key/value tiles they stream are shared).
+inline int fwd_waves(int) { return 4; }
+inline int fwd_qblocks(int head_dim) { return head_dim == 128 ? 2 : 1; }  // 32-row query blocks per wave
+inline int dq_waves(int) { return 4; }
+inline int heads_per_wg(int group, int waves) {
+  int h = 1;
+  while (h * 2 <= waves && group % (h * 2) == 0) h *= 2;
+  return h;
+}
+inline int tile_rows(int group, int waves) { return 32 * (waves / heads_per_wg(group, waves)); }
 
 // Events armed by chunk_attn_profile_events for the calling thread (null when disarmed).
 struct ProfileEvents {
@@ -43,14 +54,15 @@ struct BwdArgs {
 };
 
 // Host-side plan of one backward call and the layout of its workspace:
-// [dQ items | dK/dV items | query-tile jobs | key-tile jobs] (one uploaded blob), then the padded
-// LSE and D arrays and the transposed images of Q, dO (64-row tiles) and K (32-row tiles).
+// [dQ items | dK/dV items | 64-row query-tile jobs | 32-row key-tile jobs | 32-row query-tile jobs] (one
+// uploaded blob), then the LSE and D arrays padded to 64-row tiles and the transposed images of Q, dO
+// and K (32-row tiles).
 struct BwdPlan {
   std::vector<DqItem> dq_items;
   std::vector<DkvItem> dkv_items;
-  std::vector<TileJob> qjobs, kjobs;
-  int64_t q_tiles = 0, kv32_tiles = 0;
-  size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, blob_bytes = 0;
+  std::vector<TileJob> qjobs, kjobs, qjobs32;
+  int64_t q_tiles = 0, kv32_tiles = 0, q32_tiles = 0;
+  size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, qjobs32_off = 0, blob_bytes = 0;
   size_t lse2p_off = 0, dsp_off = 0, qt_off = 0, gt_off = 0, kt_off = 0, total = 0;
 };
 // Fills the offsets (and, if with_plan, the schedules) for a validated descriptor.

@@ -41,7 +41,7 @@ struct DqItem {
   int32_t pad0, pad1;
 };
 
-// Work item of the dK/dV kernel: 128 consecutive key rows of one segment and the 64-row query tiles
+// Work item of the dK/dV kernel: 128 consecutive key rows of one segment and the 32-row query tiles
 // (aligned to the segment's first query) that contain at least one query seeing them.
 struct DkvItem {
   int32_t kv_row0;    // first key row of the tile (global)
@@ -50,10 +50,11 @@ struct DkvItem {
   int32_t ctx;        // context length C of the segment
   int32_t q_row_seg;  // first query row of the segment (global)
   int32_t q_len;      // queries in the segment
-  int32_t qt_first;   // first 64-row query tile (inside the segment) that sees a key of this tile
-  int32_t n_qt;       // number of 64-row query tiles of the segment
-  int32_t q_tile0;    // image / slot index of the segment's first query tile
-  int32_t pad0, pad1, pad2;
+  int32_t qt_first;   // first 32-row query tile (inside the segment) that sees a key of this tile
+  int32_t n_qt;       // number of 32-row query tiles of the segment
+  int32_t q_tile0;    // index of the segment's first 64-row tile in the padded per-row arrays (LSE, D)
+  int32_t q_img0;     // index of the segment's first 32-row transposed image
+  int32_t pad0, pad1;
 };
 
 int validate(const chunk_attn_desc* d);

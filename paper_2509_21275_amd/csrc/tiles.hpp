@@ -54,6 +54,26 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_wave_base) {
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
+// Explicit LDS address-space pointers: accesses through them are always ds_* instructions, whatever the
+// compiler can or cannot prove about a generic pointer.
+typedef __attribute__((address_space(3))) __bf16 lds_bf16;
+typedef __attribute__((address_space(3))) float lds_f32;
+__device__ __forceinline__ bf16x8 lds_load8(const lds_bf16* p) {
+  return *(const __attribute__((address_space(3))) bf16x8*)p;
+}
+__device__ __forceinline__ void lds_store8(lds_bf16* p, bf16x8 v) { *(__attribute__((address_space(3))) bf16x8*)p = v; }
+__device__ __forceinline__ f32x4 lds_load4f(const lds_f32* p) {
+  return *(const __attribute__((address_space(3))) f32x4*)p;
+}
+__device__ __forceinline__ void dma4(const void* gsrc, lds_f32* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
+}
+__device__ __forceinline__ void dma16(const void* gsrc, lds_bf16* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
 // DMA a row-major tile of ROWS x (8 CHUNKS) bf16 from global rows `src + min(r, last_row) * row_stride`
 // into a swizzled LDS tile.  Called by all 256 threads of the workgroup.
 template <int ROWS, int CHUNKS>

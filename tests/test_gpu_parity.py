@@ -73,3 +73,35 @@ def test_edge_cases(oracle_mod, name, segs, Hq, Hkv, d):
 def test_nonstandard_scale(oracle_mod):
     case = synth.ChunkCase("scale", synth.hybrid_chunk(100, 300, [50, 90]), 240, 540, 8, 2, 128, 99)
     full_compare(oracle_mod, case, scale=0.05)
+
+
+def _forward_only(oracle_mod, case, q, k, v):
+    o, lse = run_gpu(case, q, k, v, backward=False)
+    orc = oracle_mod.Oracle(case.segs, q.cpu(), k.cpu(), v.cpu(), None, case.scale)
+    O, LSE = orc.forward()
+    return rel_err(o, O), float(np.abs(lse.double().cpu().numpy() - LSE).max())
+
+
+def test_forward_second_pass_forced(oracle_mod, monkeypatch):
+    """The head_dim-128 forward keeps one reference maximum per row and hands rows whose scores outgrow it to a
+    second, rescaling pass.  With the growth limit set below any score every item takes the second pass."""
+    case = synth.ChunkCase("redo_forced", synth.hybrid_chunk(200, 500, [130, 70]), 400, 900, 8, 2, 128, 31)
+    q, k, v, _ = make_inputs(case)
+    monkeypatch.setenv("CHUNK_ATTN_FWD_REF_LIMIT", "-1e30")
+    eo, el = _forward_only(oracle_mod, case, q, k, v)
+    print("forced second pass", eo, el, flush=True)
+    assert eo <= TOL_O and el <= 2e-2
+
+
+def test_forward_scores_outgrow_first_tile(oracle_mod):
+    """Scores that grow by hundreds of nats along the keys: the first tile's maximum is useless as a reference
+    for the later ones (exp2 would overflow), so the second pass must take over, on its own."""
+    n, Hq, Hkv, d = 700, 8, 2, 128
+    case = synth.ChunkCase("growing_scores", [synth.Seg(0, n, 0, n)], n, n, Hq, Hkv, d, 32)
+    q, k, v, _ = make_inputs(case)
+    ramp = torch.linspace(0.0, 3.0, n, device=q.device).view(n, 1, 1)
+    q = (torch.ones_like(q) * 4.0).to(torch.bfloat16)                       # q . k_j = 4 * 128 * ramp_j * scale
+    k = (k.float() * 0.05 + ramp).to(torch.bfloat16)                        # up to ~136 nats at the last key
+    eo, el = _forward_only(oracle_mod, case, q, k, v)
+    print("growing scores", eo, el, flush=True)
+    assert eo <= TOL_O and el <= 5e-2
