@@ -420,6 +420,10 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
     wg_barrier();
   };
 
+  // Wave A defers the second contraction of a block to the beginning of the next step: its operands are in
+  // registers by then, so its step opens with eight MFMAs that need nothing from LDS and cover the latency of
+  // the operand reads issued at the top of the step.  (The same order measured slower for wave B, which opens
+  // with the vector work of the previous block instead.)
   if (role == 0) {
     // ================= wave A: S = Q K^T, P, dV^T += dO^T P =================
     int x_off[DK], t_off[2];
@@ -429,14 +433,23 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
     for (int ks = 0; ks < 2; ++ks) t_off[ks] = GT_OFF + tile_elem<4>(l32, 2 * ks + hh);
     const lds_f32* const rv = lse_s + 4 * hh;
     lds_bf16* const pex = L + P_OFF + kb * 1024 + lane * 8;
+    bf16x8 tp[2][DB], fp[2];  // dO^T operands and P of the block whose dV^T product is pending
+    bool pend = false;
+    auto second = [&]() {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] = mfma32(tp[0][db], fp[0], acc[db]);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] = mfma32(tp[1][db], fp[1], acc[db]);
+    };
 
     auto step = [&](int g, auto u_c) {
       constexpr int u = decltype(u_c)::value;
       const bool more = g + 2 < n_iter;
       const int i0 = c_qt * BM;  // first query (inside the segment) of block g
-      if (g < n_iter && i0 + BM - 1 >= jrel_lo) {  // else: no block, or nothing of it visible to this wave's keys
-        bf16x8 a[DK], t[2][DB];
-        f32x4 r4[4];  // LSE of rows 8 g4 + 4 hh + 0..3
+      const bool vis = g < n_iter && i0 + BM - 1 >= jrel_lo;  // else: no block, or nothing of it visible to this wave
+      bf16x8 a[DK], t[2][DB];
+      f32x4 r4[4];  // LSE of rows 8 g4 + 4 hh + 0..3
+      if (vis) {
 #pragma unroll
         for (int ks = 0; ks < DK; ++ks) a[ks] = lds_load8(L + x_off[ks] + u * QT);
 #pragma unroll
@@ -445,6 +458,10 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
           for (int db = 0; db < DB; ++db) t[ks][db] = lds_load8(L + t_off[ks] + u * QT + db * 32 * BM);
+      }
+      if (pend) second();
+      pend = vis;
+      if (vis) {
         f32x16 s;
 #pragma unroll
         for (int ks = 0; ks < DK; ++ks) s = mfma32(a[ks], bfrag[ks], ks == 0 ? zero16 : s);
@@ -462,14 +479,14 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
             if (qi < jrel) w[i] = 0.f;
           }
         }
-        const bf16x8 f0 = pack8(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]);
-        const bf16x8 f1 = pack8(w[8], w[9], w[10], w[11], w[12], w[13], w[14], w[15]);
-        lds_store8(pex + (u & 1) * PT, f0);
-        lds_store8(pex + (u & 1) * PT + 512, f1);
+        fp[0] = pack8(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]);
+        fp[1] = pack8(w[8], w[9], w[10], w[11], w[12], w[13], w[14], w[15]);
+        lds_store8(pex + (u & 1) * PT, fp[0]);
+        lds_store8(pex + (u & 1) * PT + 512, fp[1]);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) acc[db] = mfma32(t[0][db], f0, acc[db]);
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) acc[db] = mfma32(t[1][db], f1, acc[db]);
+          for (int db = 0; db < DB; ++db) tp[ks][db] = t[ks][db];
       } else if (more) {
         dma_stage(std::integral_constant<int, (u + 2) % NS>{});
       }
@@ -481,6 +498,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
       if (g + 2 <= n_iter) step(g + 2, std::integral_constant<int, 2>{});
       if (g + 3 <= n_iter) step(g + 3, std::integral_constant<int, 3>{});
     }
+    if (pend) second();
   } else {
     // ================= wave B: dP = dO V^T, dS = P (dP - D), dK^T += Q^T dS =================
     // In step g it first finishes block g - 1 (vector work with wave A's P, then dK^T) and then starts block g
