@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["all", "packed", "split"], default="all",
                     help="restrict the step to one of the two chunk sets (for profiling)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="before the steps, run one plain device copy of this many MiB (a kernel of known HBM "
+                         "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus must be 1); the path shards by KV head or by "
@@ -129,6 +132,14 @@ def main():
             # the last slice's key range covers the whole sequence: it overwrites, the others accumulate
             add_call(f"split_128k_slice{i}", ci, q, k5, v5, do, dk5, dv5, 0 if i == 7 else 1)
         n_split = 8
+
+    if args.copy_probe_mib > 0:
+        src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # the probed kernel: reads and writes copy_probe_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     fwd_order = list(range(len(calls)))
     split_ids = [i for i, c in enumerate(calls) if c["name"].startswith("split")]
@@ -198,7 +209,7 @@ def main():
                      "traffic": None, "launches_per_step": n_launch,
                      "avg_launch_ms": round(bwd_k_ms / n_launch, 4),
                      "flops_per_launch_avg": dkv_flops / n_launch,
-                     "fwd_kernel": {"kernel": "fwd_kernel<128>", "achieved": round(fwd_flops / (fwd_k_ms * 1e-3) / 1e12, 2),
+                     "fwd_kernel": {"kernel": "fwd_pipe_kernel<128>", "achieved": round(fwd_flops / (fwd_k_ms * 1e-3) / 1e12, 2),
                                     "frac": round(fwd_flops / (fwd_k_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                                     "avg_launch_ms": round(fwd_k_ms / n_launch, 4)}},
         "per_call": per_call,

@@ -296,23 +296,27 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
 // so each wave keeps one fragment set (K or V) and one accumulator (dV^T or dK^T) and the whole kernel
 // fits 256 registers per lane: two waves per SIMD, whose matrix and vector phases overlap.
 // The workgroup walks the group's query heads and, per head, the 32-row query tiles that see its keys.
-// Operand tiles of a step (Q and dO rows, Q^T and dO^T images) sit in a 4-slot LDS ring filled two steps
-// ahead by global->LDS copies; the tiles wave B reads one step late (Q^T, D) are placed one slot later
-// than the others, so that everything read in step g sits in "slot g % 4".
+//
+// Only the rows of Q and dO are streamed (global->LDS copies into 4-slot rings, two steps ahead); each tile
+// serves both contractions that need it: as rows (16-byte reads, operand of Q K^T / dO V^T) and transposed
+// (ds_read_b64_tr_b16, operand of Q^T dS / dO^T P).  A tile is stored chunk-major: 16-byte chunk c of row r
+// sits at slot c * 32 + (r ^ 4 (c & 3)).  With that layout both kinds of read are bank-conflict free and
+// their addresses are one per-lane base plus constants.
 // ------------------------------------------------------------------------------------------------
 struct DkvParams {
   const __bf16 *q, *k, *v, *d_o;
-  const __bf16* qt;     // transposed Q images  [Hq][total_q32_tiles][D][32]
-  const __bf16* gt;     // transposed dO images [Hq][total_q32_tiles][D][32]
   const float* lse2p;   // [Hq][total_q_tiles * 64]
   const float* dsp;
   __bf16 *dk, *dv;
   const DkvItem* items;
-  int64_t total_q_tiles, total_q32_tiles;
+  int64_t total_q_tiles;
   int32_t num_q_heads, num_kv_heads, group;
   float scale, scale_log2;
   int32_t accumulate;
 };
+
+// element offset of (row r, 16-byte chunk c) in a 32-row chunk-major tile
+__device__ __forceinline__ int cm_elem(int r, int c) { return (c * 32 + (r ^ ((c & 3) << 2))) * 8; }
 
 template <int D>
 __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
@@ -324,19 +328,17 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
   constexpr int NS = 4;        // ring slots
   constexpr int PT = 4 * 64 * 16;      // elements of one P hand-over slot: 4 key blocks x 64 lanes x 16 values
   constexpr int CH = BM * KC;          // 16-byte chunks per operand tile
-  constexpr int PER = 4 * CH / 512;    // global->LDS copies per thread and stage
+  constexpr int PER = 2 * CH / 512;    // global->LDS copies per thread and stage
   constexpr int RV = 64;               // floats per slot of the LSE / D rows (32 used; a whole wave copies them)
-  static_assert(PER == 4 || PER == 2, "head_dim 128 or 64");
+  static_assert(PER == 2 || PER == 1, "head_dim 128 or 64");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   lds_bf16* const L = (lds_bf16*)smem;
-  constexpr int Q_OFF = 0;                 // [NS][BM][D]  Q rows        (wave A, step g)
-  constexpr int G_OFF = Q_OFF + NS * QT;   // [NS][BM][D]  dO rows       (wave B, step g)
-  constexpr int QT_OFF = G_OFF + NS * QT;  // [NS][D][BM]  Q^T image     (wave B, step g + 1)
-  constexpr int GT_OFF = QT_OFF + NS * QT; // [NS][D][BM]  dO^T image    (wave A, step g)
-  constexpr int P_OFF = GT_OFF + NS * QT;  // [2][PT]      P hand-over
-  lds_f32* const lse_s = (lds_f32*)(L + P_OFF + 2 * PT);  // [NS][RV]  (wave A, step g)
-  lds_f32* const dsum_s = lse_s + NS * RV;                // [NS][RV]  (wave B, step g + 1)
+  constexpr int Q_OFF = 0;                 // [NS][QT]  Q rows of stage n in slot n % NS   (wave A: step n, wave B: step n + 1)
+  constexpr int G_OFF = Q_OFF + NS * QT;   // [NS][QT]  dO rows                            (both waves: step n)
+  constexpr int P_OFF = G_OFF + NS * QT;   // [2][PT]   P hand-over
+  lds_f32* const lse_s = (lds_f32*)(L + P_OFF + 2 * PT);  // [NS][RV]  slot n % NS        (wave A, step n)
+  lds_f32* const dsum_s = lse_s + NS * RV;                // [NS][RV]  slot n % NS        (wave B, step n + 1)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -367,32 +369,61 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
   const int nqt = it.n_qt - it.qt_first;
   const int n_iter = nqt * G;  // stages: (head in group, query tile), head-major
 
-  // ---- staging: each thread copies PER 16-byte chunks per stage, one of each operand tile (two of four for d = 64);
-  // wave 0 also copies the stage's LSE rows and wave 1 its D rows.  No per-lane branches. ----
-  const int x0 = (PER == 4 ? wave : (wave & 3)) * 64;  // wave-uniform first chunk inside the tile
-  const int r_row = (x0 + lane) / KC;
-  const int r_chunk = unswz<KC>(r_row, (x0 + lane) % KC) * 8;
+  // ---- staging: a copy instruction of a wave fills 64 consecutive slots of a tile = two chunk columns of 32 rows;
+  // the lane fetches the chunk that belongs in its slot.  d = 128: every wave copies one piece of Q and one of dO;
+  // d = 64: waves 0..3 copy Q, waves 4..7 dO.  Wave 0 also copies the stage's LSE rows, wave 1 its D rows. ----
+  const int x0 = (PER == 2 ? wave : (wave & 3)) * 64;  // wave-uniform first slot inside the tile
+  const int s_chunk = (x0 + lane) >> 5;                // chunk column of this lane's slot
+  const int s_row = ((x0 + lane) & 31) ^ ((s_chunk & 3) << 2);
   int d_qt = it.qt_first, d_hg = 0;  // (query tile, head in group) of the next stage to copy
-  auto dma_stage = [&](auto aslot_c) {
-    constexpr int as = decltype(aslot_c)::value, bs = (as + 1) % NS;
+  auto dma_stage = [&](auto slot_c) {
+    constexpr int sl = decltype(slot_c)::value;
     const int head = kvh * G + d_hg;
     const int last_row = it.q_len - 1 - d_qt * BM;  // >= 0; rows past it repeat it (their P is 0)
     const int64_t roff = (int64_t)(it.q_row_seg + d_qt * BM) * q_stride + (int64_t)head * D;
-    const int64_t img = ((int64_t)head * p.total_q32_tiles + it.q_img0 + d_qt) * QT;
     const int64_t slot = ((int64_t)head * p.total_q_tiles + it.q_tile0) * 64 + d_qt * BM;
-    if (wave == 0) dma4(p.lse2p + slot + lane, lse_s + as * RV);
-    if (wave == 1) dma4(p.dsp + slot + lane, dsum_s + bs * RV);
-    const unsigned row_off = (unsigned)(min(r_row, last_row) * (int)q_stride + r_chunk);
-    const unsigned img_off = (unsigned)((x0 + lane) * 8);
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int tile = PER == 4 ? i : 2 * i + (wave >> 2);  // 0: Q rows, 1: dO rows, 2: Q^T image, 3: dO^T image
-      if (tile == 0) dma16(p.q + roff + row_off, L + Q_OFF + as * QT + x0 * 8);
-      else if (tile == 1) dma16(p.d_o + roff + row_off, L + G_OFF + as * QT + x0 * 8);
-      else if (tile == 2) dma16(p.qt + img + img_off, L + QT_OFF + bs * QT + x0 * 8);
-      else dma16(p.gt + img + img_off, L + GT_OFF + as * QT + x0 * 8);
+    if (wave == 0) dma4(p.lse2p + slot + lane, lse_s + sl * RV);
+    if (wave == 1) dma4(p.dsp + slot + lane, dsum_s + sl * RV);
+    const unsigned row_off = (unsigned)(min(s_row, last_row) * (int)q_stride + s_chunk * 8);
+    if (PER == 2) {
+      dma16(p.q + roff + row_off, L + Q_OFF + sl * QT + x0 * 8);
+      dma16(p.d_o + roff + row_off, L + G_OFF + sl * QT + x0 * 8);
+    } else {
+      if (wave < 4) dma16(p.q + roff + row_off, L + Q_OFF + sl * QT + x0 * 8);
+      else dma16(p.d_o + roff + row_off, L + G_OFF + sl * QT + x0 * 8);
     }
     if (++d_qt == it.n_qt) { d_qt = it.qt_first; ++d_hg; }
+  };
+
+  // ---- per-lane operand addresses (elements) inside a tile ----
+  // rows: A operand of the first contraction, X[row = l32][chunk 2 ks + hh]; k-steps of equal parity are a constant apart
+  int x_off[2];
+#pragma unroll
+  for (int par = 0; par < 2; ++par) x_off[par] = cm_elem(l32, 2 * par + hh);
+  // transposed: A operand of the second contraction, X^T[32 db + l32][k-slots of 16 ks2 ..] in accumulator order.
+  // Lane j of a 16-lane group addresses the 8 bytes (row k0 + j / 4, elements 16 grp + 4 (j % 4) ..+3); the low and
+  // the high half of the operand come from rows 8 apart.  Blocks db and k-steps ks2 are a constant apart.
+  int t_off[2];
+  {
+    const int j = lane & 15, grp = (lane >> 4) & 1;
+    const int cl = 2 * grp + ((j & 3) >> 1);  // chunk (mod 4) of the lane's 8 bytes
+    const int r0 = 4 * hh + (j >> 2);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) t_off[half] = cm_elem(r0 + 8 * half, cl) + 4 * (j & 1);
+  }
+  auto load_rows = [&](const lds_bf16* tile, bf16x8 (&a)[DK]) {
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) a[ks] = lds_load8(tile + x_off[ks & 1] + (ks >> 1) * (4 * 32 * 8));
+  };
+  auto load_transposed = [&](const lds_bf16* tile, bf16x8 (&t)[2][DB]) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const s16x4 lo = lds_read_tr(tile + t_off[0] + ks * (16 * 8) + db * (4 * 32 * 8));
+        const s16x4 hi = lds_read_tr(tile + t_off[1] + ks * (16 * 8) + db * (4 * 32 * 8));
+        t[ks][db] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
   };
 
   // key index of this lane's column relative to the context: query i of the segment sees it iff i >= jrel
@@ -426,11 +457,6 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
   // with the vector work of the previous block instead.)
   if (role == 0) {
     // ================= wave A: S = Q K^T, P, dV^T += dO^T P =================
-    int x_off[DK], t_off[2];
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) x_off[ks] = Q_OFF + tile_elem<KC>(l32, 2 * ks + hh);
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) t_off[ks] = GT_OFF + tile_elem<4>(l32, 2 * ks + hh);
     const lds_f32* const rv = lse_s + 4 * hh;
     lds_bf16* const pex = L + P_OFF + kb * 1024 + lane * 8;
     bf16x8 tp[2][DB], fp[2];  // dO^T operands and P of the block whose dV^T product is pending
@@ -450,14 +476,10 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
       bf16x8 a[DK], t[2][DB];
       f32x4 r4[4];  // LSE of rows 8 g4 + 4 hh + 0..3
       if (vis) {
-#pragma unroll
-        for (int ks = 0; ks < DK; ++ks) a[ks] = lds_load8(L + x_off[ks] + u * QT);
+        load_rows(L + Q_OFF + u * QT, a);
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) r4[g4] = lds_load4f(rv + u * RV + 8 * g4);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-          for (int db = 0; db < DB; ++db) t[ks][db] = lds_load8(L + t_off[ks] + u * QT + db * 32 * BM);
+        load_transposed(L + G_OFF + u * QT, t);
       }
       if (pend) second();
       pend = vis;
@@ -503,36 +525,27 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
     // ================= wave B: dP = dO V^T, dS = P (dP - D), dK^T += Q^T dS =================
     // In step g it first finishes block g - 1 (vector work with wave A's P, then dK^T) and then starts block g
     // (dP): right after the barrier one wave of each SIMD begins with matrix work and the other with vector work.
-    int x_off[DK], t_off[2];
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) x_off[ks] = G_OFF + tile_elem<KC>(l32, 2 * ks + hh);
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) t_off[ks] = QT_OFF + tile_elem<4>(l32, 2 * ks + hh);
     const lds_f32* const rv = dsum_s + 4 * hh;
     const lds_bf16* const pex = L + P_OFF + kb * 1024 + lane * 8;
     f32x16 dp = zero16;  // dP of the block whose dS is formed in the next step
 
     auto step = [&](int g, auto u_c) {
       constexpr int u = decltype(u_c)::value;
+      constexpr int up = (u + NS - 1) % NS;  // slot of stage g - 1
       const bool more = g + 2 < n_iter;
       const bool cur_vis = g < n_iter && (c_qt * BM + BM - 1 >= jrel_lo);
       const bool prev_vis = g >= 1 && (p_qt * BM + BM - 1 >= jrel_lo);
       bf16x8 a[DK];
-      if (cur_vis) {
-#pragma unroll
-        for (int ks = 0; ks < DK; ++ks) a[ks] = lds_load8(L + x_off[ks] + u * QT);
-      }
+      if (cur_vis) load_rows(L + G_OFF + u * QT, a);
       if (prev_vis) {
+        // ---- dS = P (dP - D) with wave A's P of block g - 1, then dK^T += Q^T dS ----
         const bf16x8 p0 = lds_load8(pex + ((u & 1) ^ 1) * PT);
         const bf16x8 p1 = lds_load8(pex + ((u & 1) ^ 1) * PT + 512);
         f32x4 r4[4];  // D of rows 8 g4 + 4 hh + 0..3
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) r4[g4] = lds_load4f(rv + u * RV + 8 * g4);
+        for (int g4 = 0; g4 < 4; ++g4) r4[g4] = lds_load4f(rv + up * RV + 8 * g4);
         bf16x8 t[2][DB];  // Q^T operands
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-          for (int db = 0; db < DB; ++db) t[ks][db] = lds_load8(L + t_off[ks] + u * QT + db * 32 * BM);
+        load_transposed(L + Q_OFF + up * QT, t);
         float w[16];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -606,11 +619,8 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
   char* ws = a.workspace;
   const TileJob* qjobs = reinterpret_cast<const TileJob*>(ws + P.qjobs_off);
   const TileJob* kjobs = reinterpret_cast<const TileJob*>(ws + P.kjobs_off);
-  const TileJob* qjobs32 = reinterpret_cast<const TileJob*>(ws + P.qjobs32_off);
   float* lse2p = reinterpret_cast<float*>(ws + P.lse2p_off);
   float* dsp = reinterpret_cast<float*>(ws + P.dsp_off);
-  __bf16* qt = reinterpret_cast<__bf16*>(ws + P.qt_off);
-  __bf16* gt = reinterpret_cast<__bf16*>(ws + P.gt_off);
   __bf16* kt = reinterpret_cast<__bf16*>(ws + P.kt_off);
   hipError_t e;
 
@@ -622,8 +632,6 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
                        P.q_tiles, d->total_q, d->num_q_heads, lse2p, dsp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  if ((e = launch_transpose(a.q, d->num_q_heads, D, 32, qjobs32, (int)P.qjobs32.size(), P.q32_tiles, qt, stream)) != hipSuccess) return e;
-  if ((e = launch_transpose(a.d_o, d->num_q_heads, D, 32, qjobs32, (int)P.qjobs32.size(), P.q32_tiles, gt, stream)) != hipSuccess) return e;
   if ((e = launch_transpose(a.k, d->num_kv_heads, D, 32, kjobs, (int)P.kjobs.size(), P.kv32_tiles, kt, stream)) != hipSuccess) return e;
 
   if (!a.accumulate) {  // rows no segment covers receive no gradient
@@ -656,15 +664,15 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
   }
   {  // dK, dV
     DkvParams p;
-    p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.qt = qt; p.gt = gt; p.lse2p = lse2p; p.dsp = dsp;
+    p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.lse2p = lse2p; p.dsp = dsp;
     p.dk = a.dk; p.dv = a.dv;
     p.items = reinterpret_cast<const DkvItem*>(ws + P.dkv_items_off);
-    p.total_q_tiles = P.q_tiles; p.total_q32_tiles = P.q32_tiles;
+    p.total_q_tiles = P.q_tiles;
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
-    // 4 ring slots of four 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
-    const size_t smem = (size_t)16 * 32 * D * 2 + 2 * 4096 * 2 + 2 * 4 * 64 * sizeof(float);
+    // 4 ring slots of two 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
+    const size_t smem = (size_t)8 * 32 * D * 2 + 2 * 4096 * 2 + 2 * 4 * 64 * sizeof(float);
     static bool attr = false;
     if ((e = set_smem(&bwd_dkv_kernel<D>, smem, &attr)) != hipSuccess) return e;
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
@@ -686,14 +694,12 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   const int dq_rows = tile_rows(group, dq_waves(d->head_dim));
   P.q_tiles = count_tiles(d, false, 64);
   P.kv32_tiles = count_tiles(d, true, 32);
-  P.q32_tiles = count_tiles(d, false, 32);
   size_t n_dq = 0, n_dkv = 0;
   if (with_plan) {
     P.dq_items = plan_dq(d, dq_rows);
     P.dkv_items = plan_dkv(d);
     P.qjobs = tile_jobs(d, false, 64, nullptr);
     P.kjobs = tile_jobs(d, true, 32, nullptr);
-    P.qjobs32 = tile_jobs(d, false, 32, nullptr);
     n_dq = P.dq_items.size();
     n_dkv = P.dkv_items.size();
   } else {
@@ -706,15 +712,11 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   P.dkv_items_off = up256(n_dq * sizeof(DqItem));
   P.qjobs_off = P.dkv_items_off + up256(n_dkv * sizeof(DkvItem));
   P.kjobs_off = P.qjobs_off + up256((size_t)P.q_tiles * sizeof(TileJob));
-  P.qjobs32_off = P.kjobs_off + up256((size_t)P.kv32_tiles * sizeof(TileJob));
-  P.blob_bytes = P.qjobs32_off + up256((size_t)P.q32_tiles * sizeof(TileJob));
+  P.blob_bytes = P.kjobs_off + up256((size_t)P.kv32_tiles * sizeof(TileJob));
   const size_t row_slots = (size_t)d->num_q_heads * P.q_tiles * 64;
   P.lse2p_off = P.blob_bytes;
   P.dsp_off = P.lse2p_off + up256(row_slots * sizeof(float));
-  P.qt_off = P.dsp_off + up256(row_slots * sizeof(float));
-  const size_t qimg = up256((size_t)d->num_q_heads * P.q32_tiles * 32 * d->head_dim * sizeof(__bf16));
-  P.gt_off = P.qt_off + qimg;
-  P.kt_off = P.gt_off + qimg;
+  P.kt_off = P.dsp_off + up256(row_slots * sizeof(float));
   P.total = P.kt_off + up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16));
 }
 
@@ -724,7 +726,6 @@ std::vector<char> bwd_blob(const BwdPlan& P) {
   std::memcpy(blob.data() + P.dkv_items_off, P.dkv_items.data(), P.dkv_items.size() * sizeof(DkvItem));
   std::memcpy(blob.data() + P.qjobs_off, P.qjobs.data(), P.qjobs.size() * sizeof(TileJob));
   std::memcpy(blob.data() + P.kjobs_off, P.kjobs.data(), P.kjobs.size() * sizeof(TileJob));
-  std::memcpy(blob.data() + P.qjobs32_off, P.qjobs32.data(), P.qjobs32.size() * sizeof(TileJob));
   return blob;
 }
 

@@ -54,16 +54,15 @@ struct BwdArgs {
 };
 
 // Host-side plan of one backward call and the layout of its workspace:
-// [dQ items | dK/dV items | 64-row query-tile jobs | 32-row key-tile jobs | 32-row query-tile jobs] (one
-// uploaded blob), then the LSE and D arrays padded to 64-row tiles and the transposed images of Q, dO
-// and K (32-row tiles).
+// [dQ items | dK/dV items | 64-row query-tile jobs | 32-row key-tile jobs] (one uploaded blob), then the
+// LSE and D arrays padded to 64-row tiles and the transposed images of K (32-row tiles).
 struct BwdPlan {
   std::vector<DqItem> dq_items;
   std::vector<DkvItem> dkv_items;
-  std::vector<TileJob> qjobs, kjobs, qjobs32;
-  int64_t q_tiles = 0, kv32_tiles = 0, q32_tiles = 0;
-  size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, qjobs32_off = 0, blob_bytes = 0;
-  size_t lse2p_off = 0, dsp_off = 0, qt_off = 0, gt_off = 0, kt_off = 0, total = 0;
+  std::vector<TileJob> qjobs, kjobs;
+  int64_t q_tiles = 0, kv32_tiles = 0;
+  size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, blob_bytes = 0;
+  size_t lse2p_off = 0, dsp_off = 0, kt_off = 0, total = 0;
 };
 // Fills the offsets (and, if with_plan, the schedules) for a validated descriptor.
 void bwd_layout(const chunk_attn_desc* d, BwdPlan& plan, bool with_plan);

@@ -113,7 +113,7 @@ std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows) {
 
 std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d) {
   std::vector<DkvItem> items;
-  int32_t q_tile0 = 0, q_img0 = 0;
+  int32_t q_tile0 = 0;
   for (int t = 0; t < d->num_segments; ++t) {
     const chunk_attn_seg& s = d->segments[t];
     const int32_t C = s.kv_len - s.q_len;
@@ -129,11 +129,9 @@ std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d) {
       it.qt_first = std::max<int32_t>(0, j0 - C) / 32;  // query i sees key j0 iff i >= j0 - C
       it.n_qt = n_qt;
       it.q_tile0 = q_tile0;
-      it.q_img0 = q_img0;
       items.push_back(it);
     }
     q_tile0 += (s.q_len + 63) / 64;
-    q_img0 += n_qt;
   }
   std::stable_sort(items.begin(), items.end(), [](const DkvItem& a, const DkvItem& b) {
     return a.n_qt - a.qt_first > b.n_qt - b.qt_first;

@@ -53,8 +53,7 @@ struct DkvItem {
   int32_t qt_first;   // first 32-row query tile (inside the segment) that sees a key of this tile
   int32_t n_qt;       // number of 32-row query tiles of the segment
   int32_t q_tile0;    // index of the segment's first 64-row tile in the padded per-row arrays (LSE, D)
-  int32_t q_img0;     // index of the segment's first 32-row transposed image
-  int32_t pad0, pad1;
+  int32_t pad0, pad1, pad2;
 };
 
 int validate(const chunk_attn_desc* d);

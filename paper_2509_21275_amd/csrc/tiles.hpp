@@ -65,6 +65,10 @@ __device__ __forceinline__ void lds_store8(lds_bf16* p, bf16x8 v) { *(__attribut
 __device__ __forceinline__ f32x4 lds_load4f(const lds_f32* p) {
   return *(const __attribute__((address_space(3))) f32x4*)p;
 }
+// LDS transpose read (ds_read_b64_tr_b16), see device_common.hpp
+__device__ __forceinline__ s16x4 lds_read_tr(const lds_bf16* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+}
 __device__ __forceinline__ void dma4(const void* gsrc, lds_f32* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
