@@ -69,6 +69,19 @@ def cpu_baseline():
                       f"(lengths {[s.q_len for s in chosen]}, {Hq}/{Hkv} heads, d={d}, {pairs} pairs per head)"}
 
 
+def recorded_traffic():
+    """HBM-side bytes per launch of the dominant kernel, as measured by the two rocprofv3 counter runs that are
+    summarised under profiles/ (this script cannot run the profiler on itself).  None if no summary is there."""
+    path = os.path.join(ROOT, "profiles", "bwd_dkv_kernel_bench_workload_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +90,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["all", "packed", "split"], default="all",
                     help="restrict the step to one of the two chunk sets (for profiling)")
+    ap.add_argument("--fast-inputs", action="store_true",
+                    help="draw the N(0,1) inputs with torch.randn (one kernel per tensor) instead of the counter-based "
+                         "generator (thousands of small kernels, slow under rocprofv3 counter collection)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the steps, run one plain device copy of this many MiB (a kernel of known HBM "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
@@ -93,6 +109,13 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.fast_inputs:
+        torch.manual_seed(synth.BASE_SEED)
+
+        def normal_bf16(seed, tensor_id, shape, device):
+            return torch.randn(shape, dtype=torch.float32, device=device).to(torch.bfloat16)
+    else:
+        normal_bf16 = synth.normal_bf16
     evpool = ca.HipEvents()
 
     # ---------------- workloads ----------------
@@ -113,22 +136,22 @@ def main():
 
     if args.only in ("all", "packed"):
         c4 = synth.case_by_index(4)
-        q = synth.normal_bf16(c4.seed, 0, (c4.total_q, c4.num_q_heads, c4.head_dim), dev)
-        k = synth.normal_bf16(c4.seed, 1, (c4.total_kv, c4.num_kv_heads, c4.head_dim), dev)
-        v = synth.normal_bf16(c4.seed, 2, (c4.total_kv, c4.num_kv_heads, c4.head_dim), dev)
-        do = synth.normal_bf16(c4.seed, 3, (c4.total_q, c4.num_q_heads, c4.head_dim), dev)
+        q = normal_bf16(c4.seed, 0, (c4.total_q, c4.num_q_heads, c4.head_dim), dev)
+        k = normal_bf16(c4.seed, 1, (c4.total_kv, c4.num_kv_heads, c4.head_dim), dev)
+        v = normal_bf16(c4.seed, 2, (c4.total_kv, c4.num_kv_heads, c4.head_dim), dev)
+        do = normal_bf16(c4.seed, 3, (c4.total_q, c4.num_q_heads, c4.head_dim), dev)
         add_call("packed_64k", c4, q, k, v, do, torch.empty_like(k), torch.empty_like(v), 0)
     n_split = 0
     if args.only in ("all", "split"):
         c5 = synth.case_by_index(5, 0)
-        k5 = synth.normal_bf16(c5.seed, 1, (c5.total_kv, c5.num_kv_heads, c5.head_dim), dev)
-        v5 = synth.normal_bf16(c5.seed, 2, (c5.total_kv, c5.num_kv_heads, c5.head_dim), dev)
+        k5 = normal_bf16(c5.seed, 1, (c5.total_kv, c5.num_kv_heads, c5.head_dim), dev)
+        v5 = normal_bf16(c5.seed, 2, (c5.total_kv, c5.num_kv_heads, c5.head_dim), dev)
         dk5 = torch.empty_like(k5); dv5 = torch.empty_like(v5)
         for i in range(8):
             ci = synth.case_by_index(5, i)
             # tensor ids 10+i / 20+i: each slice has its own query and dO rows of the long sequence
-            q = synth.normal_bf16(ci.seed, 10 + i, (ci.total_q, ci.num_q_heads, ci.head_dim), dev)
-            do = synth.normal_bf16(ci.seed, 20 + i, (ci.total_q, ci.num_q_heads, ci.head_dim), dev)
+            q = normal_bf16(ci.seed, 10 + i, (ci.total_q, ci.num_q_heads, ci.head_dim), dev)
+            do = normal_bf16(ci.seed, 20 + i, (ci.total_q, ci.num_q_heads, ci.head_dim), dev)
             # the last slice's key range covers the whole sequence: it overwrites, the others accumulate
             add_call(f"split_128k_slice{i}", ci, q, k5, v5, do, dk5, dv5, 0 if i == 7 else 1)
         n_split = 8
@@ -197,7 +220,7 @@ def main():
         "metric": "chunk attention fwd+bwd causal TFLOP/s, 1 MI355X",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic (torch.randn)" if args.fast_inputs else "synthetic",
         "config": {"workload": {"all": "packed_64k_skewed(32/8 heads,d128) + split_128k_x8(64/8 heads,d128), fwd+bwd",
                                 "packed": "packed_64k_skewed(32/8 heads,d128), fwd+bwd",
                                 "split": "split_128k_x8(64/8 heads,d128), fwd+bwd"}[args.only],
@@ -206,7 +229,7 @@ def main():
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "roofline": {"kernel": "bwd_dkv_kernel<128>", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "launches_per_step": n_launch,
+                     "traffic": recorded_traffic(), "launches_per_step": n_launch,
                      "avg_launch_ms": round(bwd_k_ms / n_launch, 4),
                      "flops_per_launch_avg": dkv_flops / n_launch,
                      "fwd_kernel": {"kernel": "fwd_pipe_kernel<128>", "achieved": round(fwd_flops / (fwd_k_ms * 1e-3) / 1e12, 2),

@@ -8,15 +8,13 @@
 //
 //   bwd_pre   D_i = <dO_i, O_i> and LSE_i log2(e) per (head, row), stored in arrays padded to 64-row
 //             tiles per segment (+inf / 0 in the padding, so padded rows yield P = 0);
-//   transposes (transpose_kernel.hip) of K (32-row tiles) and of Q, dO (64-row tiles);
+//   transpose (transpose_kernel.hip) of K into 32-row tile images, for the dQ kernel;
 //   bwd_dq    query-stationary, like the forward: S^T = K Q^T and dP^T = V dO^T per 32-key tile,
 //             dS^T = P^T (dP^T - D), dQ^T += K^T dS^T with dS^T fed back from the accumulator registers;
-//   bwd_dkv   key-stationary: one workgroup per 128 keys of one key/value head, K and V fragments in
-//             registers, walking the query heads of the group and the 64-row query tiles that see
-//             those keys: S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS with P and dS fed back
-//             from the accumulator registers.
-// P is recomputed from the saved log-sum-exp in both kernels.  All operands reach LDS by global->LDS
-// copies and are read with 16-byte LDS reads from swizzled tiles (tiles.hpp).
+//   bwd_dkv   key-stationary: one workgroup per 128 keys of one key/value head, walking the query heads of
+//             the group and the 32-row query tiles that see those keys; two wave roles per key block,
+//             S = Q K^T, P, dV^T += dO^T P  and  dP = dO V^T, dS, dK^T += Q^T dS (see the kernel).
+// P is recomputed from the saved log-sum-exp in both kernels.  All operands reach LDS by global->LDS copies.
 #include <cstring>
 #include <cstdlib>
 #include <type_traits>

@@ -31,27 +31,12 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// acc *= alpha for an accumulator tile that lives in accumulation registers (kernels that use more than 256
-// registers per lane keep every MFMA result there).  Written as one opaque read-multiply-write per element so
-// that the register allocator never wants a vector-register copy of the tile (it would otherwise keep one
-// alive across the whole main loop just for this rarely executed rescale).  The s_nop cover the wait states
-// between an MFMA writing the register and this read, and between this write and the next MFMA reading it.
-__device__ __forceinline__ void scale_acc_tile(f32x16& acc, float alpha) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    float e = acc[i], t;
-    asm volatile(
-        "s_nop 15\n\ts_nop 3\n\tv_accvgpr_read_b32 %1, %0\n\ts_nop 1\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\t"
-        "v_accvgpr_write_b32 %0, %1\n\ts_nop 7"
-        : "+a"(e), "=&v"(t)
-        : "v"(alpha));
-    acc[i] = e;
-  }
-}
-
-// Element i of an accumulator tile that lives in accumulation registers, read without giving the register
-// allocator a vector-register use of the tile (see scale_acc_tile).  Call mfma_settle() once after the last
-// MFMA and before the first read.
+// Element i of an accumulator tile that lives in accumulation registers (kernels that use more than 256
+// registers per lane keep every MFMA result there), read with one opaque register move.  A plain read would
+// give the register allocator a vector-register use of the tile, and it then keeps a vector-register copy of
+// the whole tile alive across the main loop.  The move is also ordered against other opaque statements and
+// scheduling fences, which pins the arithmetic that depends on it.  The caller guarantees the distance to the
+// MFMA that wrote the register (mfma_settle() after the last MFMA, or enough instructions in between).
 __device__ __forceinline__ float read_acc_elem(const f32x16& acc, int i) {
   float e = acc[i], t;
   asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(e));

@@ -2,15 +2,20 @@
 // chunk mask of the paper's section 3.1 (each segment's queries see their own context and the causal
 // part of their own slice; packed sequences see nothing of each other).
 //
-// One workgroup (4 waves) takes one forward work item -- a tile of query rows of one segment -- for up
-// to four query heads that share one key/value head, and streams that segment's visible keys/values
-// through LDS in tiles of 64 rows: K row-major, V as the pre-transposed image (transpose_kernel.hip),
-// both copied global->LDS without passing through registers and double-buffered.  Each wave owns 32
-// query rows of one head and keeps their Q fragments in registers.  Scores are computed transposed,
-// S^T = K Q^T, so that after the MFMA every lane holds one query column: the row maximum and row sum
-// are a loop over the lane's own registers plus one exchange with the lane 32 away, and the bf16
-// probabilities are already laid out as the B operand of O^T += V^T P^T (device_common.hpp, "C-order").
-// Two workgroups share a compute unit, so one wave's softmax arithmetic overlaps another's MFMAs.
+// A workgroup takes one forward work item -- a tile of query rows of one segment -- for the query heads of
+// one group that share a key/value head, and streams that segment's visible keys/values through LDS in
+// tiles of 64 rows: K row-major, V as the pre-transposed image (transpose_kernel.hip), both copied
+// global->LDS without passing through registers and double-buffered.  Scores are computed transposed,
+// S^T = K Q^T, so that after the MFMA every lane holds one query column: row maximum and row sum are a loop
+// over the lane's own registers plus one exchange with the lane 32 away, and the bf16 probabilities are
+// already laid out as the B operand of O^T += V^T P^T (device_common.hpp, "C-order").
+//
+// Two kernels:
+//   fwd_kernel       online softmax with a lazily moved reference maximum, one 32-row query block per wave,
+//                    two waves per SIMD.  Used for head_dim 64, and for head_dim 128 as the second pass below.
+//   fwd_pipe_kernel  head_dim 128: one wave per SIMD with 64 query rows, software pipelined over the key
+//                    tiles, reference maximum fixed by the first tile; rows whose scores outgrow it are
+//                    flagged and recomputed by fwd_kernel, launched right after over the flagged items only.
 #include <type_traits>
 
 #include "kernels.hpp"
@@ -18,8 +23,9 @@
 
 namespace chunk_attn {
 
-template <int D, int WAVES, int QB>
-__global__ __launch_bounds__(WAVES * 64, QB == 1 ? 8 / WAVES : 1) void fwd_kernel(FwdParams p) {
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void fwd_kernel(FwdParams p) {
+  constexpr int QB = 1;        // 32-row query blocks per wave
   constexpr int NT = WAVES * 64;  // threads
   constexpr int BN = 64;       // key rows per LDS tile
   constexpr int KC = D / 8;    // 16-byte chunks per K row
@@ -36,7 +42,7 @@ __global__ __launch_bounds__(WAVES * 64, QB == 1 ? 8 / WAVES : 1) void fwd_kerne
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
   const int l32 = lane & 31, hh = lane >> 5;
-  if (QB == 1) stagger_wave_priority();
+  stagger_wave_priority();
 
   const int inner_n = p.num_kv_heads * p.head_splits;
   const int inner = blockIdx.x % inner_n;
@@ -134,12 +140,11 @@ __global__ __launch_bounds__(WAVES * 64, QB == 1 ? 8 / WAVES : 1) void fwd_kerne
   // (the buffers are KT elements = a power of two bytes apart), so the accumulators are carried by a single
   // loop and never pass through a conditional.
   static_assert((KT & (KT - 1)) == 0, "buffer pitch must be a power of two");
-  const bool all_tiles = QB > 1;  // with QB > 1 a wave also runs the tiles past its own last one (fully masked: P = 0)
   int buf = 0;
   for (int t = 0; t < nt_wg; ++t) {
     if (t + 1 < nt_wg) dma_tile(t + 1, buf ^ 1);
 
-    if (all_tiles || t < nt_w) {
+    if (t < nt_w) {
       const __bf16* Kt = Ks;
       const __bf16* Vt = Vs;
       // ---- S^T = K Q^T : [64 keys] x [32 QB queries]; every K fragment feeds QB products ----
@@ -183,14 +188,9 @@ __global__ __launch_bounds__(WAVES * 64, QB == 1 ? 8 / WAVES : 1) void fwd_kerne
           const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
           l_run[qb] *= alpha;
 #pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            if constexpr (QB == 1) {
+          for (int db = 0; db < DB; ++db)
 #pragma unroll
-              for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
-            } else {
-              scale_acc_tile(oacc[qb][db], alpha);
-            }
-          }
+            for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
           m_run[qb] = m_new;
         }
         const float mc = m_run[qb] * c;
@@ -238,11 +238,7 @@ __global__ __launch_bounds__(WAVES * 64, QB == 1 ? 8 / WAVES : 1) void fwd_kerne
   }
 
   // ---- epilogue: O = O^T / l, LSE = ln(l) + m scale ----
-  auto oval = [&](int qb, int db, int i) {
-    if constexpr (QB == 1) return oacc[qb][db][i];
-    else return read_acc_elem(oacc[qb][db], i);
-  };
-  if (QB > 1) mfma_settle();
+  auto oval = [&](int qb, int db, int i) { return oacc[qb][db][i]; };
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int r = wave_row0 + 32 * qb + l32;
@@ -554,7 +550,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
   }
 }
 
-template <int D, int WAVES, int QB>
+template <int D, int WAVES>
 static hipError_t launch_fwd_t(const FwdParams& p, int num_blocks, hipStream_t stream);
 
 static hipError_t launch_fwd_pipe(const FwdParams& p, int num_blocks, hipStream_t stream) {
@@ -570,25 +566,25 @@ static hipError_t launch_fwd_pipe(const FwdParams& p, int num_blocks, hipStream_
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // second pass over the same items, 8 waves of 32 rows: a workgroup returns at once unless its flag is raised
-  return launch_fwd_t<128, 8, 1>(p, num_blocks, stream);
+  return launch_fwd_t<128, 8>(p, num_blocks, stream);
 }
 
-template <int D, int WAVES, int QB>
+template <int D, int WAVES>
 static hipError_t launch_fwd_t(const FwdParams& p, int num_blocks, hipStream_t stream) {
   const size_t smem = (size_t)4 * 64 * D * 2;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_kernel<D, WAVES, QB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_kernel<D, WAVES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((fwd_kernel<D, WAVES, QB>), dim3(num_blocks), dim3(WAVES * 64), smem, stream, p);
+  hipLaunchKernelGGL((fwd_kernel<D, WAVES>), dim3(num_blocks), dim3(WAVES * 64), smem, stream, p);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, hipStream_t stream) {
-  return head_dim == 128 ? launch_fwd_pipe(p, num_blocks, stream) : launch_fwd_t<64, 4, 1>(p, num_blocks, stream);
+  return head_dim == 128 ? launch_fwd_pipe(p, num_blocks, stream) : launch_fwd_t<64, 4>(p, num_blocks, stream);
 }
 
 }  // namespace chunk_attn

@@ -28,8 +28,10 @@ struct FwdParams {
 // rows of query tile per forward work item for a given head layout
 // Shape of a query-stationary workgroup (forward and dQ kernels): `waves` waves of 32 query rows each, spread
 // over as many query heads of one group as divide both (so that the key/value tiles they stream are shared).
+// forward: 4 waves; for head_dim 128 each wave owns two 32-row query blocks (fwd_pipe_kernel; its second pass,
+// fwd_kernel with 8 waves of one block, covers the same rows per workgroup)
 inline int fwd_waves(int) { return 4; }
-inline int fwd_qblocks(int head_dim) { return head_dim == 128 ? 2 : 1; }  // 32-row query blocks per wave
+inline int fwd_qblocks(int head_dim) { return head_dim == 128 ? 2 : 1; }
 inline int dq_waves(int head_dim) { return head_dim == 128 ? 8 : 4; }
 inline int heads_per_wg(int group, int waves) {
   int h = 1;
