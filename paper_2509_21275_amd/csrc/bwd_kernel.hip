@@ -318,19 +318,22 @@ struct DkvParams {
 // element offset of (row r, 16-byte chunk c) in a 32-row chunk-major tile
 __device__ __forceinline__ int cm_elem(int r, int c) { return (c * 32 + (r ^ ((c & 3) << 2))) * 8; }
 
-template <int D>
-__global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
+template <int D, int KB>  // KB: 32-key blocks per workgroup (2 KB waves)
+__global__ __launch_bounds__(KB * 128, 4 / KB) void bwd_dkv_kernel(DkvParams p) {
+  constexpr int NW = 2 * KB;   // waves
+  constexpr int NTH = NW * 64; // threads
   constexpr int BM = 32;       // query rows per step
   constexpr int KC = D / 8;    // 16-byte chunks per operand row
   constexpr int DK = D / 16;   // k-steps over the head dimension
   constexpr int DB = D / 32;   // 32-row blocks of dK^T / dV^T
   constexpr int QT = BM * D;   // elements per operand tile
   constexpr int NS = 4;        // ring slots
-  constexpr int PT = 4 * 64 * 16;      // elements of one P hand-over slot: 4 key blocks x 64 lanes x 16 values
+  constexpr int PT = KB * 64 * 16;     // elements of one P hand-over slot: KB key blocks x 64 lanes x 16 values
   constexpr int CH = BM * KC;          // 16-byte chunks per operand tile
-  constexpr int PER = 2 * CH / 512;    // global->LDS copies per thread and stage
+  constexpr int PER = 2 * CH / NTH;    // global->LDS copies per thread and stage
+  constexpr int NP = CH / 64;          // 64-slot pieces per tile
   constexpr int RV = 64;               // floats per slot of the LSE / D rows (32 used; a whole wave copies them)
-  static_assert(PER == 2 || PER == 1, "head_dim 128 or 64");
+  static_assert(PER >= 1 && 2 * NP % NW == 0, "the pieces of the two tiles divide evenly among the waves");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   lds_bf16* const L = (lds_bf16*)smem;
@@ -342,7 +345,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int role = wave >> 2, kb = wave & 3;
+  const int role = wave / KB, kb = wave % KB;
   const int l32 = lane & 31, hh = lane >> 5;
 
   const int kvh = blockIdx.x % p.num_kv_heads;
@@ -370,11 +373,16 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
   const int n_iter = nqt * G;  // stages: (head in group, query tile), head-major
 
   // ---- staging: a copy instruction of a wave fills 64 consecutive slots of a tile = two chunk columns of 32 rows;
-  // the lane fetches the chunk that belongs in its slot.  d = 128: every wave copies one piece of Q and one of dO;
-  // d = 64: waves 0..3 copy Q, waves 4..7 dO.  Wave 0 also copies the stage's LSE rows, wave 1 its D rows. ----
-  const int x0 = (PER == 2 ? wave : (wave & 3)) * 64;  // wave-uniform first slot inside the tile
-  const int s_chunk = (x0 + lane) >> 5;                // chunk column of this lane's slot
-  const int s_row = ((x0 + lane) & 31) ^ ((s_chunk & 3) << 2);
+  // the lane fetches the chunk that belongs in its slot.  The 2 NP pieces of a stage (NP of Q, then NP of dO) are
+  // dealt to the waves round robin.  Wave 0 also copies the stage's LSE rows, wave 1 its D rows. ----
+  int s_off[PER];  // element offset of the lane's chunk inside its row ...
+  int s_row[PER];  // ... and the row, per piece
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int x = ((i * NW + wave) % NP) * 64 + lane;
+    s_off[i] = (x >> 5) * 8;
+    s_row[i] = (x & 31) ^ (((x >> 5) & 3) << 2);
+  }
   int d_qt = it.qt_first, d_hg = 0;  // (query tile, head in group) of the next stage to copy
   auto dma_stage = [&](auto slot_c) {
     constexpr int sl = decltype(slot_c)::value;
@@ -384,13 +392,12 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(DkvParams p) {
     const int64_t slot = ((int64_t)head * p.total_q_tiles + it.q_tile0) * 64 + d_qt * BM;
     if (wave == 0) dma4(p.lse2p + slot + lane, lse_s + sl * RV);
     if (wave == 1) dma4(p.dsp + slot + lane, dsum_s + sl * RV);
-    const unsigned row_off = (unsigned)(min(s_row, last_row) * (int)q_stride + s_chunk * 8);
-    if (PER == 2) {
-      dma16(p.q + roff + row_off, L + Q_OFF + sl * QT + x0 * 8);
-      dma16(p.d_o + roff + row_off, L + G_OFF + sl * QT + x0 * 8);
-    } else {
-      if (wave < 4) dma16(p.q + roff + row_off, L + Q_OFF + sl * QT + x0 * 8);
-      else dma16(p.d_o + roff + row_off, L + G_OFF + sl * QT + x0 * 8);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int piece = i * NW + wave;  // wave-uniform: < NP: Q, else dO
+      const unsigned row_off = (unsigned)(min(s_row[i], last_row) * (int)q_stride + s_off[i]);
+      if (piece < NP) dma16(p.q + roff + row_off, L + Q_OFF + sl * QT + piece * 512);
+      else dma16(p.d_o + roff + row_off, L + G_OFF + sl * QT + (piece - NP) * 512);
     }
     if (++d_qt == it.n_qt) { d_qt = it.qt_first; ++d_hg; }
   };
@@ -673,15 +680,16 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
     // 4 ring slots of two 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
-    const size_t smem = (size_t)8 * 32 * D * 2 + 2 * 4096 * 2 + 2 * 4 * 64 * sizeof(float);
+    constexpr int KB = DKV_KEYS / 32;
+    const size_t smem = (size_t)8 * 32 * D * 2 + 2 * KB * 1024 * 2 + 2 * 4 * 64 * sizeof(float);
     static bool attr = false;
-    if ((e = set_smem(&bwd_dkv_kernel<D>, smem, &attr)) != hipSuccess) return e;
+    if ((e = set_smem(&bwd_dkv_kernel<D, KB>, smem, &attr)) != hipSuccess) return e;
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     ProfileEvents pe = profile_events();
     profile_events() = ProfileEvents{};
     if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dkv_kernel<D>), dim3((unsigned)blocks), dim3(512), smem, stream, p);
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, KB>), dim3((unsigned)blocks), dim3(KB * 128), smem, stream, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return e;
   }
@@ -698,7 +706,7 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   size_t n_dq = 0, n_dkv = 0;
   if (with_plan) {
     P.dq_items = plan_dq(d, dq_rows);
-    P.dkv_items = plan_dkv(d);
+    P.dkv_items = plan_dkv(d, dkv_keys(d->head_dim));
     P.qjobs = tile_jobs(d, false, 64, nullptr);
     P.kjobs = tile_jobs(d, true, 32, nullptr);
     n_dq = P.dq_items.size();
@@ -706,7 +714,7 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   } else {
     for (int t = 0; t < d->num_segments; ++t) {
       n_dq += (d->segments[t].q_len + dq_rows - 1) / dq_rows;
-      n_dkv += (d->segments[t].kv_len + 127) / 128;
+      n_dkv += (d->segments[t].kv_len + dkv_keys(d->head_dim) - 1) / dkv_keys(d->head_dim);
     }
   }
   P.dq_items_off = 0;

@@ -5,6 +5,10 @@
 #include "device_common.hpp"
 #include "plan.hpp"
 
+#ifndef DKV_KEYS
+#define DKV_KEYS 128
+#endif
+
 namespace chunk_attn {
 
 struct FwdParams {
@@ -38,6 +42,8 @@ inline int heads_per_wg(int group, int waves) {
   while (h * 2 <= waves && group % (h * 2) == 0) h *= 2;
   return h;
 }
+// key rows per work item of the dK/dV kernel (32 per pair of waves)
+inline int dkv_keys(int) { return DKV_KEYS; }
 inline int tile_rows(int group, int waves) { return 32 * (waves / heads_per_wg(group, waves)); }
 
 // Events armed by chunk_attn_profile_events for the calling thread (null when disarmed).

@@ -111,17 +111,17 @@ std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows) {
   return items;
 }
 
-std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d) {
+std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys) {
   std::vector<DkvItem> items;
   int32_t q_tile0 = 0;
   for (int t = 0; t < d->num_segments; ++t) {
     const chunk_attn_seg& s = d->segments[t];
     const int32_t C = s.kv_len - s.q_len;
     const int32_t n_qt = (s.q_len + 31) / 32;
-    for (int32_t j0 = 0; j0 < s.kv_len; j0 += 128) {
+    for (int32_t j0 = 0; j0 < s.kv_len; j0 += keys) {
       DkvItem it{};
       it.kv_row0 = s.kv_start + j0;
-      it.kv_rows = std::min<int32_t>(128, s.kv_len - j0);
+      it.kv_rows = std::min<int32_t>(keys, s.kv_len - j0);
       it.j0 = j0;
       it.ctx = C;
       it.q_row_seg = s.q_start;

@@ -41,11 +41,11 @@ struct DqItem {
   int32_t pad0, pad1;
 };
 
-// Work item of the dK/dV kernel: 128 consecutive key rows of one segment and the 32-row query tiles
+// Work item of the dK/dV kernel: up to 128 consecutive key rows of one segment and the 32-row query tiles
 // (aligned to the segment's first query) that contain at least one query seeing them.
 struct DkvItem {
   int32_t kv_row0;    // first key row of the tile (global)
-  int32_t kv_rows;    // valid key rows (1..128)
+  int32_t kv_rows;    // valid key rows
   int32_t j0;         // index of the tile's first key inside the segment
   int32_t ctx;        // context length C of the segment
   int32_t q_row_seg;  // first query row of the segment (global)
@@ -62,7 +62,7 @@ int64_t pair_count(const chunk_attn_desc* d);
 // Tiles of `tile_rows` query rows per segment, most work first.
 std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows);
 std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows);
-std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d);
+std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys);  // `keys` consecutive key rows per item
 // `width`-row tiles of every segment's key range (kv = true) or query range (kv = false), in segment order;
 // seg_tile0[t] receives the image index of segment t's first tile.
 std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, int width, std::vector<int32_t>* seg_tile0);
