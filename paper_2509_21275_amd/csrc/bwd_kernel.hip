@@ -28,6 +28,10 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
+#ifndef DKV_PIPE_DIST
+#define DKV_PIPE_DIST 3
+#endif
+
 // ------------------------------------------------------------------------------------------------
 // bwd_pre: one workgroup per (64-row query tile, head); 4 threads per row.
 // ------------------------------------------------------------------------------------------------
@@ -607,6 +611,499 @@ __global__ __launch_bounds__(KB * 128, 4 / KB) void bwd_dkv_kernel(DkvParams p) 
   }
 }
 
+// LDS accesses as opaque instructions, for bwd_dkv_pipe_kernel.  The compiler makes a wave wait for ALL of its
+// outstanding global->LDS copies before an LDS read it cannot tell apart from their destinations (the
+// transpose read in particular), which would serialise the copies of later stages with the reads of the
+// current one.  Issued like this, the reads are invisible to that logic; the kernel orders them itself with
+// explicit s_waitcnt lgkmcnt(n) (LDS operations of a wave complete in order).  `addr` is a byte address.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_asm_read16(unsigned addr) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ f32x4 lds_asm_read16f(unsigned addr) {
+  f32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_asm_read_tr(unsigned addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ void lds_asm_write16(unsigned addr, bf16x8 v) {
+  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ unsigned lds_addr(const lds_bf16* p) { return (unsigned)(uintptr_t)p; }
+__device__ __forceinline__ unsigned lds_addr(const lds_f32* p) { return (unsigned)(uintptr_t)p; }
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bwd_dkv_pipe (head_dim 128)
+//
+// Same work split as bwd_dkv_kernel, laid out for one wave per SIMD: a workgroup of 4 waves covers 128
+// keys; each wave owns 64 keys (two 32-key blocks), waves 0, 1 in role A (S, P, dV^T), waves 2, 3 in role B
+// (dP, dS, dK^T).  Every operand fragment read from LDS feeds two MFMAs (the wave's two key blocks), and
+// with nobody else on the SIMD the wave overlaps its own matrix and vector work by software pipelining:
+// in step g it runs
+//     role A:  S(g) = Q K^T           P(g-1) = exp2(S(g-1) c - LSE)       dV^T += dO^T P(g-2)
+//     role B:  dP(g-2) = dO V^T       dS(g-3) = P(g-3) (dP(g-3) - D)      dK^T += Q^T dS(g-4)
+// (stage n = the n-th (head, 32-row query tile) of the workgroup's walk).  The three pieces of a step are
+// independent of each other.  A wave issues at most one instruction every four cycles and an MFMA holds the
+// matrix pipe for 32, so the step is laid out instruction by instruction: 16 mini-steps of one operand
+// fragment and the two MFMAs it feeds, each MFMA followed by its share of everything else (the vector work
+// of one score, an LDS read, a copy), so that the next MFMA finds the pipe just free.  Fragments are fetched
+// four mini-steps ahead (the first four of a step before the barrier that ends the previous one).  Role A
+// writes P(g-2) to LDS in step g, role B picks it up one step later.  Stages live in a ring of DIST + 5 slots
+// (5 in use, DIST on their way from global memory).
+// A step runs the same straight-line code whatever the stage.  Stages outside the walk compute on zeros or
+// on stale (finite) data and contribute nothing: LDS starts zeroed, and role A starts the S accumulation of
+// such a stage from -inf (P = 0), just as it does for the entries a query does not see.
+// S and dP are kept in vector registers, where the vector work reads them directly; the compiler would keep
+// every MFMA result of a kernel this size in accumulation registers (one extra move per element), so those
+// MFMAs are written as opaque instructions.
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
+  constexpr int NW = 4;        // waves
+  constexpr int BM = 32;       // query rows per stage
+  constexpr int KC = D / 8;    // 16-byte chunks per operand row
+  constexpr int DK = D / 16;   // k-steps over the head dimension
+  constexpr int DB = D / 32;   // 32-row blocks of dK^T / dV^T
+  constexpr int QT = BM * D;   // elements per operand tile
+  constexpr int DIST = DKV_PIPE_DIST;  // stages copied ahead of the step that first reads them
+  constexpr int NS = DIST + 5; // ring slots: stages g - 4 .. g in use, g + 1 .. g + DIST on their way
+  constexpr int NF = 2 * DB + DK;      // operand fragments (mini-steps) per step
+  constexpr int AHEAD = 4;             // fragments in flight
+  constexpr int PS = 2 * 4 * 64 * 8;   // elements of one P hand-over slot: 2 wave pairs x 4 fragments x 64 lanes x 8
+  constexpr int CH = BM * KC;          // 16-byte chunks per operand tile
+  constexpr int NP = CH / 64;          // 64-slot pieces per tile
+  constexpr int PER = 2 * NP / NW;     // global->LDS copies of operand pieces per wave and stage
+  constexpr int RV = 64;               // floats per slot of the LSE / D rows (32 used; a whole wave copies them)
+  static_assert(D == 128 && NF == 16 && PER == 4, "the mini-step schedule below is written for head_dim 128");
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  lds_bf16* const L = (lds_bf16*)smem;
+  constexpr int Q_OFF = 0;                 // [NS][QT]  Q rows of stage n in slot n % NS
+  constexpr int G_OFF = Q_OFF + NS * QT;   // [NS][QT]  dO rows
+  constexpr int P_OFF = G_OFF + NS * QT;   // [2][PS]   P hand-over
+  constexpr int R_OFF = P_OFF + 2 * PS;    // [NS][RV] floats LSE rows, then [NS][RV] floats D rows
+  lds_f32* const lse_s = (lds_f32*)(L + R_OFF);
+  lds_f32* const dsum_s = lse_s + NS * RV;
+  constexpr int LDS_ELEMS = R_OFF + 2 * NS * RV * 2;  // in bf16 units
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int role = wave >> 1, pair = wave & 1;
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  const int kvh = blockIdx.x % p.num_kv_heads;
+  const DkvItem it = p.items[blockIdx.x / p.num_kv_heads];
+  const int G = p.group;
+  const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
+  const float c = p.scale_log2;
+
+  // zero everything but the ring slots the prologue fills
+  {
+    bf16x8 z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.0f;
+    for (int x = tid; x < (NS - DIST) * QT / 8; x += NW * 64) {
+      lds_store8(L + Q_OFF + DIST * QT + x * 8, z);
+      lds_store8(L + G_OFF + DIST * QT + x * 8, z);
+    }
+    for (int x = tid; x < (LDS_ELEMS - P_OFF) / 8; x += NW * 64) lds_store8(L + P_OFF + x * 8, z);
+  }
+
+  const int nqt = it.n_qt - it.qt_first;
+  const int n_iter = nqt * G;  // stages: (head in group, query tile), head-major
+
+  // ---- staging (as in bwd_dkv_kernel): the 2 NP pieces of a stage are dealt to the waves round robin; even
+  // waves also copy the stage's LSE rows, odd waves its D rows (twice each: no wave-dependent branch).  Past the
+  // last stage the last one is copied again (into a slot nobody reads any more), so that every step issues the
+  // same number of copies. ----
+  // byte offset of the lane's chunk of piece i from the tile's first row, for a full tile and for the segment's
+  // last tile (rows past the last query repeat it; their P is 0)
+  unsigned v_full[PER], v_last[PER];
+  {
+    const int last_row = it.q_len - 1 - (it.n_qt - 1) * BM;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int x = ((i * NW + wave) % NP) * 64 + lane;
+      const int off = (x >> 5) * 8, row = (x & 31) ^ (((x >> 5) & 3) << 2);
+      v_full[i] = (unsigned)(row * (int)q_stride + off) * 2u;
+      v_last[i] = (unsigned)(min(row, last_row) * (int)q_stride + off) * 2u;
+    }
+  }
+  int d_qt = it.qt_first, d_hg = 0, d_n = 0;  // (query tile, head in group, index) of the next stage to copy
+  int d_slot = 0;
+  int64_t d_roff = 0, d_rv = 0;  // wave-uniform element offsets of the stage's first row in Q / dO and in the row arrays
+  auto dma_locate = [&]() __attribute__((always_inline)) {
+    const int head = kvh * G + d_hg;
+    d_roff = (int64_t)(it.q_row_seg + d_qt * BM) * q_stride + (int64_t)head * D;
+    d_rv = ((int64_t)head * p.total_q_tiles + it.q_tile0) * 64 + d_qt * BM;
+  };
+  dma_locate();
+  const float* const rows_src = ((wave & 1) ? p.dsp : p.lse2p) + lane;
+  lds_f32* const rows_dst = (wave & 1) ? dsum_s : lse_s;
+  auto dma_rows = [&]() __attribute__((always_inline)) { dma4(rows_src + d_rv, rows_dst + d_slot * RV); };
+  auto dma_piece = [&](int i) __attribute__((always_inline)) {
+    const int piece = i * NW + wave;  // wave-uniform; i < NP / NW: a piece of Q, else of dO
+    const unsigned voff = d_qt == it.n_qt - 1 ? v_last[i] : v_full[i];
+    const char* base = reinterpret_cast<const char*>((i < NP / NW ? p.q : p.d_o) + d_roff);
+    lds_bf16* dst = L + (i < NP / NW ? Q_OFF + piece * 512 : G_OFF + (piece - NP) * 512) + d_slot * QT;
+    dma16(base + voff, dst);
+  };
+  auto dma_advance = [&]() __attribute__((always_inline)) {
+    if (d_n + 1 < n_iter) {
+      ++d_n;
+      if (++d_qt == it.n_qt) {
+        d_qt = it.qt_first;
+        ++d_hg;
+        dma_locate();
+      } else {
+        d_roff += BM * q_stride;
+        d_rv += BM;
+      }
+    }
+    d_slot = d_slot == NS - 1 ? 0 : d_slot + 1;
+  };
+
+  // ---- per-lane operand addresses (elements) inside a tile, as in bwd_dkv_kernel ----
+  int x_off[2];
+#pragma unroll
+  for (int par = 0; par < 2; ++par) x_off[par] = cm_elem(l32, 2 * par + hh);
+  int t_off[2];
+  {
+    const int j = lane & 15, grp = (lane >> 4) & 1;
+    const int cl = 2 * grp + ((j & 3) >> 1);
+    const int r0 = 4 * hh + (j >> 2);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) t_off[half] = cm_elem(r0 + 8 * half, cl) + 4 * (j & 1);
+  }
+  auto prev_slot = [&](int s) __attribute__((always_inline)) { return s == 0 ? NS - 1 : s - 1; };
+
+  // Everything from here on is instantiated once per role, with its own accumulators.
+  auto body = [&](auto role_c) __attribute__((always_inline)) {
+    constexpr int ROLE = decltype(role_c)::value;
+    const lds_bf16* const a_tile = L + (ROLE ? G_OFF : Q_OFF);  // rows operand: Q (role A) or dO (role B)
+    const lds_bf16* const t_tile = L + (ROLE ? Q_OFF : G_OFF);  // transposed operand: dO^T (role A) or Q^T (role B)
+    const lds_f32* const rv_rows = (ROLE ? dsum_s : lse_s) + 4 * hh;
+    lds_bf16* const pex = L + P_OFF + pair * (4 * 512) + lane * 8;
+
+    // this wave's K (role A) or V (role B) fragments, B operands: lane holds X[key = 64 pair + 32 kb + l32][16 ks + 8 hh ..+7]
+    bf16x8 bfrag[2][DK];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const __bf16* src = ROLE ? p.v : p.k;
+      const int64_t grow = it.kv_row0 + min(64 * pair + 32 * kb + l32, it.kv_rows - 1);
+      const int64_t off = grow * kv_stride + (int64_t)kvh * D + 8 * hh;
+#pragma unroll
+      for (int ks = 0; ks < DK; ++ks) bfrag[kb][ks] = *reinterpret_cast<const bf16x8*>(src + off + 16 * ks);
+    }
+
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 acc[2][DB];  // dV^T (role A) or dK^T (role B): [D] x [32 keys of block kb]
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[kb][db] = zero16;
+
+    // key index of this lane's column of block 0 relative to the context: query i of the segment sees the column of
+    // block kb iff i >= jrel + 32 kb
+    const int jrel = it.j0 + 64 * pair + l32 - it.ctx;
+    const int jrel_hi = it.j0 + 64 * pair + 63 - it.ctx;  // of the wave's last key
+
+    // prologue: stages 0 .. DIST - 1 (after the fragment loads, so that the waits below count only copies);
+    // every wave issues PER + 1 copies per stage
+#pragma unroll
+    for (int s = 0; s < DIST; ++s) {
+      dma_rows();
+#pragma unroll
+      for (int i = 0; i < PER; ++i) dma_piece(i);
+      dma_advance();
+    }
+    // A wait the compiler can see, for all copies and loads issued so far: without it the compiler's own bookkeeping
+    // of outstanding loads makes it put a full vmcnt(0) wait inside the loop (before role A's first S MFMA).
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    wg_barrier();
+
+    // pipeline state
+    int sA = ROLE ? NS - 2 : 0;  // slot of stage g - 2 ROLE (rows operand); one before: row values and the next step's
+                                 // transposed operand; two before: this step's transposed operand
+    int s_qt = it.qt_first;      // role A: query tile of stage g (whose S is computed in step g)
+    // Role A masks through the accumulator: the first MFMA of S starts from a tile that holds -inf where the query
+    // does not see the key (and everywhere for a stage past the end of the walk) and 0 elsewhere.  The tile is
+    // rebuilt only for the stages that need it.
+    f32x16 mask_c[2] = {zero16, zero16};
+    bool mask_set = false;
+    f32x16 x[2][2];              // S or dP: [buffer][key block]
+    bf16x8 f[2][2][2];           // P or dS as B operands: [buffer][key block][k-step]
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[b][kb][i] = ROLE ? 0.f : -INFINITY;  // role A: P = 0 before the first stage
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) f[b][kb][ks][i] = (__bf16)0.0f;
+      }
+    bf16x8 fr[8];  // ring of operand fragments
+
+    // byte addresses of this lane's operand reads inside slot 0
+    const unsigned t_lo0 = lds_addr(t_tile + t_off[0]), t_hi0 = lds_addr(t_tile + t_off[1]);
+    const unsigned a_ev0 = lds_addr(a_tile + x_off[0]), a_od0 = lds_addr(a_tile + x_off[1]);
+    const unsigned rv0 = lds_addr(rv_rows), pex0 = lds_addr(pex);
+    constexpr unsigned SLOT = QT * 2;  // bytes per ring slot
+    // transposed fragment m = ks2 * DB + db of the tile at (lo, hi)
+    auto load_t = [&](unsigned lo_addr, unsigned hi_addr, auto m_c) __attribute__((always_inline)) {
+      constexpr int m = decltype(m_c)::value;
+      constexpr int off = ((m / DB) * (16 * 8) + (m % DB) * (4 * 32 * 8)) * 2;
+      const s16x4 lo = lds_asm_read_tr<off>(lo_addr);
+      const s16x4 hi = lds_asm_read_tr<off>(hi_addr);
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // rows fragment of k-step ks of the tile at (even, odd)
+    auto load_a = [&](unsigned ev_addr, unsigned od_addr, auto ks_c) __attribute__((always_inline)) {
+      constexpr int ks = decltype(ks_c)::value;
+      constexpr int off = (ks >> 1) * (4 * 32 * 8) * 2;
+      return lds_asm_read16<off>((ks & 1) ? od_addr : ev_addr);
+    };
+
+    // the first fragments of step 0 (zeros)
+    {
+      const unsigned sT = prev_slot(prev_slot(sA)) * SLOT;
+      static_for<0, AHEAD>([&](auto m_c) __attribute__((always_inline)) {
+        fr[decltype(m_c)::value] = load_t(t_lo0 + sT, t_hi0 + sT, m_c);
+      });
+    }
+
+    // LDS operations of a step, in program order: 8 for the hand-over and the row values, then one fragment per
+    // mini-step (two instructions for a transposed fragment: fragments 0 .. 2 DB - 1 of this step and of the next).
+    // Before mini-step m uses fragment m, everything issued up to its read must be complete; LGKM(m) is the number
+    // of LDS instructions issued after that read and before the wait (which precedes mini-step m's own read).
+    // In program order: mini-step m reads fragment m + 4 (two instructions for a transposed fragment, i.e. fragments
+    // 0 .. 7 of this step and 0 .. 3 of the next one, else one); mini-step 0 then issues the 4 hand-over instructions
+    // and mini-step 1 the 4 row-value reads.  lgkm_wait(m) = number of those instructions that lie between the read of
+    // fragment m and the start of mini-step m, where the wait stands (-1: an earlier wait already covers fragment m).
+    // Mini-step 4 also waits for the hand-over and the row values: only fragments 6 and 7 may be outstanding then.
+    auto lgkm_wait = [](int m) {
+      constexpr int tab[16] = {6, 10, 14, 14, 4, -1, 4, 3, 3, 3, 3, 3, 3, 4, 5, 6};
+      return tab[m];
+    };
+    auto step = [&](int g, f32x16 (&cur)[2], f32x16 (&nxt)[2], bf16x8 (&f_old)[2][2],
+                    bf16x8 (&f_new)[2][2]) __attribute__((always_inline)) {
+      const int sR = prev_slot(sA), sT = prev_slot(sR);
+      const unsigned oA = sA * SLOT, oR = sR * SLOT, oT = sT * SLOT;
+      const unsigned t_lo = t_lo0 + oT, t_hi = t_hi0 + oT, a_ev = a_ev0 + oA, a_od = a_od0 + oA;
+      const unsigned n_lo = t_lo0 + oR, n_hi = t_hi0 + oR;
+      if (ROLE == 0) {
+        // entry (query 8 (i / 4) + 4 hh + i % 4 of the tile, column of block kb) is visible iff 8 (i / 4) + i % 4 >= lim[kb]
+        const bool valid = g < n_iter;
+        if (!valid || s_qt * BM < jrel_hi) {
+          const int lim0 = valid ? jrel - s_qt * BM - 4 * hh : 0x40000000;
+          const int lim1 = valid ? lim0 + 32 : 0x40000000;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            mask_c[0][i] = 8 * (i >> 2) + (i & 3) < lim0 ? -INFINITY : 0.f;
+            mask_c[1][i] = 8 * (i >> 2) + (i & 3) < lim1 ? -INFINITY : 0.f;
+          }
+          mask_set = true;
+        } else if (mask_set) {
+          mask_c[0] = zero16;
+          mask_c[1] = zero16;
+          mask_set = false;
+        }
+      }
+      // hand-over (mini-step 0) and row values (mini-step 1) are issued between the MFMAs, so that the matrix pipe
+      // restarts right after the barrier; the vector work starts at mini-step 4
+      bf16x8 ph[2][2];
+      f32x4 r4[4];  // LSE (role A) or D (role B) of rows 8 g4 + 4 hh + 0..3
+      const unsigned pa = pex0 + (ROLE == 0 ? (g & 1) : ((g & 1) ^ 1)) * (PS * 2);
+      const unsigned ra = rv0 + sR * (RV * 4);
+      unsigned pw[2][8];
+      float e_hold[2];  // role A: exponentials of the previous pair (converted one mini-step later: a transcendental
+                        // result cannot be consumed by the very next instruction)
+      // vector work of score 2 dw + q of block kb (pair j = 8 kb + dw), pinned to where it is written (the compiler
+      // would gather the vector work elsewhere)
+      auto vec_half = [&](auto j_c, auto q_c) __attribute__((always_inline)) {
+        constexpr int j = decltype(j_c)::value, q = decltype(q_c)::value;
+        constexpr int kb = j >> 3, dw = j & 7, i = 2 * dw + q;
+        if (ROLE == 0) {
+          if constexpr (j > 0 && q == 0) {  // the previous pair's exponentials
+            bf16x2 w;
+            w[0] = (__bf16)e_hold[0]; w[1] = (__bf16)e_hold[1];
+            unsigned wu = __builtin_bit_cast(unsigned, w);
+            asm volatile("" : "+v"(wu));
+            pw[(j - 1) >> 3][(j - 1) & 7] = wu;
+          }
+          e_hold[q] = __builtin_amdgcn_exp2f(cur[kb][i] * c - r4[i >> 2][i & 3]);
+          asm volatile("" : "+v"(e_hold[q]));
+        } else {
+          const float e = (float)ph[kb][i >> 3][i & 7] * (cur[kb][i] - r4[i >> 2][i & 3]);
+          if constexpr (q == 0) {
+            e_hold[0] = e;
+            asm volatile("" : "+v"(e_hold[0]));
+          } else {
+            bf16x2 w;
+            w[0] = (__bf16)e_hold[0]; w[1] = (__bf16)e;
+            unsigned wu = __builtin_bit_cast(unsigned, w);
+            asm volatile("" : "+v"(wu));
+            pw[kb][dw] = wu;
+          }
+        }
+      };
+      auto vec_pair = [&](auto j_c) __attribute__((always_inline)) {
+        vec_half(j_c, std::integral_constant<int, 0>{});
+        vec_half(j_c, std::integral_constant<int, 1>{});
+      };
+      asm volatile("s_nop 7" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<0, NF>([&](auto m_c) __attribute__((always_inline)) {
+        constexpr int m = decltype(m_c)::value;
+        {  // wait for fragment m (and, in mini-step 4, for the hand-over and the row values)
+          constexpr int lgkm = lgkm_wait(m);
+          static_assert(lgkm <= 15, "lgkmcnt is a 4-bit counter");
+          if constexpr (m == 4) {
+            if (ROLE == 0)
+              asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(fr[m & 7]), "+v"(r4[0]), "+v"(r4[1]), "+v"(r4[2]), "+v"(r4[3]) : "n"(lgkm));
+            else
+              asm volatile("s_waitcnt lgkmcnt(%9)" : "+v"(fr[m & 7]), "+v"(r4[0]), "+v"(r4[1]), "+v"(r4[2]), "+v"(r4[3]),
+                           "+v"(ph[0][0]), "+v"(ph[0][1]), "+v"(ph[1][0]), "+v"(ph[1][1]) : "n"(lgkm));
+          } else if constexpr (lgkm >= 0) {
+            asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(fr[m & 7]) : "n"(lgkm));
+          }
+        }
+        {  // read the fragment of mini-step m + AHEAD (past the end: the next step's first transposed fragments)
+          constexpr int mm = m + AHEAD;
+          if constexpr (mm < 2 * DB) fr[mm & 7] = load_t(t_lo, t_hi, std::integral_constant<int, mm>{});
+          else if constexpr (mm < NF) fr[mm & 7] = load_a(a_ev, a_od, std::integral_constant<int, mm - 2 * DB>{});
+          else fr[mm & 7] = load_t(n_lo, n_hi, std::integral_constant<int, mm - NF>{});
+        }
+        const bf16x8 fa = fr[m & 7];
+        // S / dP live in vector registers (the vector work reads them directly) and K / V fragments in accumulation
+        // registers; written as opaque instructions since the compiler keeps every MFMA result of a kernel with more
+        // than 256 registers in accumulation registers.  Their results are first read one step later.
+        auto mma = [&](auto kb_c) __attribute__((always_inline)) {
+          constexpr int kb = decltype(kb_c)::value;
+          if constexpr (m < 2 * DB) {
+            constexpr int ks = m / DB, db = m % DB;
+            acc[kb][db] = mfma32(fa, f_old[kb][ks], acc[kb][db]);
+          } else {
+            constexpr int ks = m - 2 * DB;
+            if (ks == 0 && ROLE == 0)
+              asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]), "v"(mask_c[kb]));
+            else if (ks == 0)
+              asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]));
+            else
+              asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]));
+          }
+        };
+        // The mini-step's two MFMAs are kept apart by half of its other work: issued back to back, the second one would
+        // hold up the wave (the only one on this SIMD) until the first has left the matrix pipe.
+        constexpr std::integral_constant<int, 0> c0{};
+        constexpr std::integral_constant<int, 1> c1{};
+        mma(c0);
+        if constexpr (m == 0) {
+          if (ROLE == 0) {
+            lds_asm_write16<0>(pa, f_old[0][0]);
+            lds_asm_write16<1024>(pa, f_old[0][1]);
+            lds_asm_write16<2048>(pa, f_old[1][0]);
+            lds_asm_write16<3072>(pa, f_old[1][1]);
+          } else {
+            ph[0][0] = lds_asm_read16<0>(pa);
+            ph[0][1] = lds_asm_read16<1024>(pa);
+            ph[1][0] = lds_asm_read16<2048>(pa);
+            ph[1][1] = lds_asm_read16<3072>(pa);
+          }
+        }
+        if constexpr (m == 1) {
+          r4[0] = lds_asm_read16f<0>(ra);
+          r4[1] = lds_asm_read16f<32>(ra);
+          r4[2] = lds_asm_read16f<64>(ra);
+          r4[3] = lds_asm_read16f<96>(ra);
+        }
+        if (m == 2) dma_rows();
+        // pairs 0 .. 7 in mini-steps 4 .. 11 (one half next to each MFMA), pairs 8 .. 15 two per mini-step after that
+        if constexpr (m >= 4 && m < 12) vec_half(std::integral_constant<int, m - 4>{}, c0);
+        if constexpr (m >= 12) vec_pair(std::integral_constant<int, 8 + 2 * (m - 12)>{});
+        __builtin_amdgcn_sched_barrier(0);
+        mma(c1);
+        if (m >= 3 && m < 3 + 2 * PER && ((m - 3) & 1) == 0) dma_piece((m - 3) >> 1);
+        if constexpr (m >= 4 && m < 12) vec_half(std::integral_constant<int, m - 4>{}, c1);
+        if constexpr (m >= 12) vec_pair(std::integral_constant<int, 9 + 2 * (m - 12)>{});
+        if constexpr (m == 10) {  // bookkeeping for the next step (the copies of this step have been issued)
+          dma_advance();
+          sA = sA == NS - 1 ? 0 : sA + 1;
+          if (ROLE == 0 && ++s_qt == it.n_qt) s_qt = it.qt_first;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      if (ROLE == 0) {
+        bf16x2 w;
+        w[0] = (__bf16)e_hold[0]; w[1] = (__bf16)e_hold[1];
+        pw[1][7] = __builtin_bit_cast(unsigned, w);
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          u32x4 v = {pw[kb][4 * ks], pw[kb][4 * ks + 1], pw[kb][4 * ks + 2], pw[kb][4 * ks + 3]};
+          f_new[kb][ks] = __builtin_bit_cast(bf16x8, v);
+        }
+      // Stage g + 1 must have landed; the copies of the DIST - 1 stages after it may still be in flight.  This wave's
+      // hand-over stores completed long ago (mini-step 2 waited for them).
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * (PER + 1)) : "memory");
+      wg_barrier();
+    };
+    // role A's last product is dV^T of stage n - 1 in step n + 1, role B's dK^T of stage n - 1 in step n + 3
+    const int n_steps = n_iter + 4;
+    for (int g = 0; g < n_steps; g += 2) {
+      step(g, x[0], x[1], f[0], f[1]);
+      step(g + 1, x[1], x[0], f[1], f[0]);
+    }
+
+    // ---- epilogue: dV = dV^T (role A), dK = scale * dK^T (role B), written (or added) as bf16 ----
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int kr = 64 * pair + 32 * kb + l32;
+      if (kr < it.kv_rows) {
+        const int64_t off = ((int64_t)it.kv_row0 + kr) * kv_stride + (int64_t)kvh * D;
+        __bf16* const out = ROLE ? p.dk : p.dv;
+        const float fs = ROLE ? p.scale : 1.0f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            float v0 = acc[kb][db][4 * g] * fs, v1 = acc[kb][db][4 * g + 1] * fs, v2 = acc[kb][db][4 * g + 2] * fs,
+                  v3 = acc[kb][db][4 * g + 3] * fs;
+            bf16x4* op = reinterpret_cast<bf16x4*>(out + off + 32 * db + 8 * g + 4 * hh);
+            if (p.accumulate) {
+              const bf16x4 old = *op;
+              v0 += (float)old[0]; v1 += (float)old[1]; v2 += (float)old[2]; v3 += (float)old[3];
+            }
+            *op = pack4(v0, v1, v2, v3);
+          }
+      }
+    }
+  };
+  if (role == 0) body(std::integral_constant<int, 0>{});
+  else body(std::integral_constant<int, 1>{});
+}
+
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
@@ -679,17 +1176,27 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
-    // 4 ring slots of two 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
-    constexpr int KB = DKV_KEYS / 32;
-    const size_t smem = (size_t)8 * 32 * D * 2 + 2 * KB * 1024 * 2 + 2 * 4 * 64 * sizeof(float);
-    static bool attr = false;
-    if ((e = set_smem(&bwd_dkv_kernel<D, KB>, smem, &attr)) != hipSuccess) return e;
+    static_assert(DKV_KEYS == 128, "both kernels cover 128 keys per workgroup");
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    static bool attr = false;
     ProfileEvents pe = profile_events();
     profile_events() = ProfileEvents{};
-    if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, KB>), dim3((unsigned)blocks), dim3(KB * 128), smem, stream, p);
+    if constexpr (D == 128) {
+      // ring slots of two 32-row operand tiles, 2 P hand-over slots, one slot of LSE and D rows per ring slot
+      constexpr int NS = DKV_PIPE_DIST + 5;
+      const size_t smem = (size_t)2 * NS * 32 * D * 2 + 2 * 4096 * 2 + 2 * NS * 64 * sizeof(float);
+      if ((e = set_smem(&bwd_dkv_pipe_kernel<D>, smem, &attr)) != hipSuccess) return e;
+      if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
+      hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    } else {
+      // 4 ring slots of two 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
+      constexpr int KB = DKV_KEYS / 32;
+      const size_t smem = (size_t)8 * 32 * D * 2 + 2 * KB * 1024 * 2 + 2 * 4 * 64 * sizeof(float);
+      if ((e = set_smem(&bwd_dkv_kernel<D, KB>, smem, &attr)) != hipSuccess) return e;
+      if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
+      hipLaunchKernelGGL((bwd_dkv_kernel<D, KB>), dim3((unsigned)blocks), dim3(KB * 128), smem, stream, p);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return e;
   }
