@@ -1105,6 +1105,339 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// bwd_dq_pipe (head_dim 128)
+//
+// The dQ kernel in the style of bwd_dkv_pipe_kernel: one wave per SIMD, a workgroup of 4 waves, each wave
+// owning two 32-row query blocks ("units": the workgroup's 8 units are the same (head, row block) pairs the
+// 8 waves of bwd_dq_kernel take), so that every K / V fragment read from LDS feeds two MFMAs.  Stage t is
+// the t-th 32-key tile of the segment; in step t a wave runs
+//     dP^T(t) = V(t) dO^T        S^T(t+1) = K(t+1) Q^T        dQ^T += K(t-1)^T dS^T(t-1)      (matrix pipe)
+//     P^T(t) = exp2(S^T(t) c - LSE)  and, once dP^T(t) is complete,  dS^T(t) = P^T(t) (dP^T(t) - D)   (vector)
+// as 24 mini-steps of one LDS operand fragment and the two MFMAs it feeds (one per unit), each MFMA followed
+// by its share of the vector work.  K^T is read from the K tile itself with the LDS transpose read (tiles
+// are stored chunk-major as in the dK/dV kernels), so no transposed image of K is needed.  K and V tiles
+// live in a ring of DIST + 3 slots.  Steps whose tile needs the causal mask (the last one or two of the
+// walk) or lies past the end run a second variant of the step that masks in the vector work.
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
+  constexpr int NW = 4;        // waves
+  constexpr int BN = 32;       // key rows per stage
+  constexpr int KC = D / 8;    // 16-byte chunks per K / V row
+  constexpr int DK = D / 16;   // k-steps over the head dimension
+  constexpr int DB = D / 32;   // 32-row blocks of dQ^T
+  constexpr int KT = BN * D;   // elements per tile
+  constexpr int DIST = 3;      // stages copied ahead
+  constexpr int NS = DIST + 3; // ring slots: stages t - 1 .. t + 1 in use, t + 2 .. t + 1 + DIST on their way
+  constexpr int NF = 2 * DK + 2 * DB;  // operand fragments (mini-steps) per step: V rows, K rows, K^T
+  constexpr int AHEAD = 4;             // fragments in flight
+  constexpr int NP = BN * KC / 64;     // 64-slot pieces per tile
+  constexpr int PER = 2 * NP / NW;     // global->LDS copies per wave and stage
+  static_assert(D == 128 && NF == 24 && PER == 4, "the mini-step schedule below is written for head_dim 128");
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  lds_bf16* const L = (lds_bf16*)smem;
+  constexpr int K_OFF = 0;               // [NS][KT]  K rows of stage n in slot n % NS (chunk-major)
+  constexpr int V_OFF = K_OFF + NS * KT; // [NS][KT]  V rows
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  const int inner_n = p.num_kv_heads * p.head_splits;
+  const int inner = blockIdx.x % inner_n;
+  const DqItem it = p.items[blockIdx.x / inner_n];
+  const int kvh = inner % p.num_kv_heads, hs = inner / p.num_kv_heads;
+  int head[2], row0[2];  // of the wave's two units
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int unit = 2 * wave + u;
+    head[u] = kvh * p.group + hs * p.heads_per_wg + unit % p.heads_per_wg;
+    row0[u] = (unit / p.heads_per_wg) * 32;
+  }
+
+  const int n_wg = it.n0 + it.q_rows - 1;    // keys visible to the last valid row
+  const int nt = (n_wg + BN - 1) / BN;       // stages
+
+  const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
+  const __bf16* __restrict__ Kg = p.k + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
+  const __bf16* __restrict__ Vg = p.v + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
+
+  // the ring slots the prologue does not fill are read before anything is copied into them (K(-1) in step 0)
+  {
+    bf16x8 z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.0f;
+    for (int x = tid; x < (NS - DIST - 1) * KT / 8; x += NW * 64) {
+      lds_store8(L + K_OFF + (DIST + 1) * KT + x * 8, z);
+      lds_store8(L + V_OFF + (DIST + 1) * KT + x * 8, z);
+    }
+  }
+
+  // Q and dO fragments (B operands): lane holds X[row = l32 of the unit][16 ks + 8 hh ..+7]; LSE and D of that row
+  bf16x8 qf[2][DK], gf[2][DK];
+  float lse2[2], dsum[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int r_own = min(row0[u] + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
+    const int64_t off = (int64_t)(it.q_row0 + r_own) * q_stride + (int64_t)head[u] * D + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      qf[u][ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
+      gf[u][ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
+    }
+    const int64_t slot = (int64_t)head[u] * p.total_q_tiles * 64 + it.q_slot0 + r_own;
+    lse2[u] = p.lse2p[slot];
+    dsum[u] = p.dsp[slot];
+  }
+
+  // ---- staging: the 2 NP pieces of a stage (NP of K, then NP of V) are dealt to the waves round robin; a piece is
+  // 64 consecutive slots of a chunk-major tile = two chunk columns of 32 rows.  Past the last stage the last one is
+  // copied again (into a slot nobody reads for anything that counts). ----
+  unsigned v_full[PER], v_last[PER];  // byte offset of the lane's chunk from the tile's first row: full tile, last tile
+  {
+    const int last_row = n_wg - 1 - (nt - 1) * BN;  // rows past the last key repeat it (masked)
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int x = ((i * NW + wave) % NP) * 64 + lane;
+      const int off = (x >> 5) * 8, row = (x & 31) ^ (((x >> 5) & 3) << 2);
+      v_full[i] = (unsigned)(row * (int)kv_stride + off) * 2u;
+      v_last[i] = (unsigned)(min(row, last_row) * (int)kv_stride + off) * 2u;
+    }
+  }
+  int d_t = 0, d_slot = 0;   // stage to copy next (clamped to the last one) and its slot
+  int64_t d_off = 0;         // element offset of its first row
+  auto dma_piece = [&](int i) __attribute__((always_inline)) {
+    const int piece = i * NW + wave;  // wave-uniform; i < NP / NW: a piece of K, else of V
+    const unsigned voff = d_t == nt - 1 ? v_last[i] : v_full[i];
+    const char* base = reinterpret_cast<const char*>((i < NP / NW ? Kg : Vg) + d_off);
+    lds_bf16* dst = L + (i < NP / NW ? K_OFF + piece * 512 : V_OFF + (piece - NP) * 512) + d_slot * KT;
+    dma16(base + voff, dst);
+  };
+  auto dma_advance = [&]() __attribute__((always_inline)) {
+    if (d_t + 1 < nt) {
+      ++d_t;
+      d_off += BN * kv_stride;
+    }
+    d_slot = d_slot == NS - 1 ? 0 : d_slot + 1;
+  };
+
+  // per-lane operand addresses inside a tile (as in the dK/dV kernels)
+  int x_off[2], t_off[2];
+#pragma unroll
+  for (int par = 0; par < 2; ++par) x_off[par] = cm_elem(l32, 2 * par + hh);
+  {
+    const int j = lane & 15, grp = (lane >> 4) & 1;
+    const int cl = 2 * grp + ((j & 3) >> 1);
+    const int r0 = 4 * hh + (j >> 2);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) t_off[half] = cm_elem(r0 + 8 * half, cl) + 4 * (j & 1);
+  }
+  const unsigned k_ev0 = lds_addr(L + K_OFF + x_off[0]), k_od0 = lds_addr(L + K_OFF + x_off[1]);
+  const unsigned v_ev0 = lds_addr(L + V_OFF + x_off[0]), v_od0 = lds_addr(L + V_OFF + x_off[1]);
+  const unsigned t_lo0 = lds_addr(L + K_OFF + t_off[0]), t_hi0 = lds_addr(L + K_OFF + t_off[1]);
+  constexpr unsigned SLOT = KT * 2;  // bytes per ring slot
+  auto load_rows = [&](unsigned ev_addr, unsigned od_addr, auto ks_c) __attribute__((always_inline)) {
+    constexpr int ks = decltype(ks_c)::value;
+    constexpr int off = (ks >> 1) * (4 * 32 * 8) * 2;
+    return lds_asm_read16<off>((ks & 1) ? od_addr : ev_addr);
+  };
+  auto load_t = [&](unsigned lo_addr, unsigned hi_addr, auto m_c) __attribute__((always_inline)) {
+    constexpr int m = decltype(m_c)::value;  // ks2 * DB + db
+    constexpr int off = ((m / DB) * (16 * 8) + (m % DB) * (4 * 32 * 8)) * 2;
+    const s16x4 lo = lds_asm_read_tr<off>(lo_addr);
+    const s16x4 hi = lds_asm_read_tr<off>(hi_addr);
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  // A wait the compiler can see for the loads above, before the first copy is issued (see bwd_dkv_pipe_kernel)
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  // prologue: stages 0 .. DIST; stages 0 and 1 must have landed before the first step
+#pragma unroll
+  for (int s = 0; s <= DIST; ++s) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) dma_piece(i);
+    dma_advance();
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * PER) : "memory");
+  wg_barrier();
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 dq[2][DB];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) dq[u][db] = zero16;
+  f32x16 x[2][2];   // S^T: [buffer][unit]
+  f32x16 dp[2];     // dP^T: [unit]
+  bf16x8 f[2][2][2];  // dS^T as B operands: [buffer][unit][k-step]
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[b][u][ks][i] = (__bf16)0.0f;
+  const float c = p.scale_log2;
+  bf16x8 fr[8];  // ring of operand fragments
+
+  // S^T(0) = K(0) Q^T, then the first fragments of step 0 (V rows of stage 0)
+  {
+    bf16x8 a[DK];
+    static_for<0, DK>([&](auto ks_c) __attribute__((always_inline)) { a[decltype(ks_c)::value] = load_rows(k_ev0, k_od0, ks_c); });
+    static_for<0, AHEAD>([&](auto ks_c) __attribute__((always_inline)) { fr[decltype(ks_c)::value] = load_rows(v_ev0, v_od0, ks_c); });
+    asm volatile("s_waitcnt lgkmcnt(%8)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]) : "n"(AHEAD));
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(x[0][u]) : "v"(a[ks]), "a"(qf[u][ks]));
+        else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(x[0][u]) : "v"(a[ks]), "a"(qf[u][ks]));
+      }
+    mfma_settle();
+  }
+
+  // In program order mini-step m reads fragment m + 4: one instruction for the rows fragments (0 .. 15 of this step,
+  // 0 .. 3 of the next), two for the transposed ones (16 .. 23).  lgkm_wait(m) = number of LDS instructions between the
+  // read of fragment m and the start of mini-step m, where the wait stands.
+  auto lgkm_wait = [](int m) {
+    constexpr int tab[24] = {3, 3, 3, 3, 3, 3, 3, 3, 3, 3, 3, 3, 3, 4, 5, 6, 6, 6, 6, 6, 6, 5, 4, 3};
+    return tab[m];
+  };
+  int sV = 0;  // slot of stage t
+  auto step = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2], bf16x8 (&f_old)[2][2], bf16x8 (&f_new)[2][2],
+                  auto masked_c) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;
+    const int sK = sV == NS - 1 ? 0 : sV + 1;   // stage t + 1
+    const int sM = sV == 0 ? NS - 1 : sV - 1;   // stage t - 1
+    const unsigned v_ev = v_ev0 + sV * SLOT, v_od = v_od0 + sV * SLOT, k_ev = k_ev0 + sK * SLOT, k_od = k_od0 + sK * SLOT;
+    const unsigned t_lo = t_lo0 + sM * SLOT, t_hi = t_hi0 + sM * SLOT, n_ev = v_ev0 + sK * SLOT, n_od = v_od0 + sK * SLOT;
+    // MASKED: element i (key 8 (i / 4) + 4 hh + i % 4 of the tile) of unit u is visible iff 8 (i / 4) + i % 4 < lim[u]
+    int lim[2];
+    if (MASKED) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) lim[u] = t < nt ? it.n0 + row0[u] + l32 - BN * t - 4 * hh : -0x40000000;
+    }
+    float pf[2][16];   // P^T(t)
+    unsigned pw[2][8]; // dS^T(t), packed pairs
+    auto exp_half = [&](auto j_c, auto q_c) __attribute__((always_inline)) {  // P of element 2 dw + q of unit u (pair j = 8 u + dw)
+      constexpr int j = decltype(j_c)::value, q = decltype(q_c)::value;
+      constexpr int u = j >> 3, i = 2 * (j & 7) + q;
+      float tt = cur[u][i] * c - lse2[u];
+      if (MASKED) {
+        if (8 * (i >> 2) + (i & 3) >= lim[u]) tt = -INFINITY;
+      }
+      pf[u][i] = __builtin_amdgcn_exp2f(tt);
+      asm volatile("" : "+v"(pf[u][i]));  // pinned here (the compiler would gather the vector work elsewhere)
+    };
+    auto ds_pair = [&](auto j_c) __attribute__((always_inline)) {
+      constexpr int j = decltype(j_c)::value;
+      constexpr int u = j >> 3, dw = j & 7;
+      bf16x2 w;
+      w[0] = (__bf16)(pf[u][2 * dw] * (dp[u][2 * dw] - dsum[u]));
+      w[1] = (__bf16)(pf[u][2 * dw + 1] * (dp[u][2 * dw + 1] - dsum[u]));
+      unsigned wu = __builtin_bit_cast(unsigned, w);
+      asm volatile("" : "+v"(wu));
+      pw[u][dw] = wu;
+    };
+    asm volatile("s_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, NF>([&](auto m_c) __attribute__((always_inline)) {
+      constexpr int m = decltype(m_c)::value;
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(fr[m & 7]) : "n"(lgkm_wait(m)));
+      {  // read the fragment of mini-step m + AHEAD (past the end: the next step's first V fragments)
+        constexpr int mm = m + AHEAD;
+        if constexpr (mm < DK) fr[mm & 7] = load_rows(v_ev, v_od, std::integral_constant<int, mm>{});
+        else if constexpr (mm < 2 * DK) fr[mm & 7] = load_rows(k_ev, k_od, std::integral_constant<int, mm - DK>{});
+        else if constexpr (mm < NF) fr[mm & 7] = load_t(t_lo, t_hi, std::integral_constant<int, mm - 2 * DK>{});
+        else fr[mm & 7] = load_rows(n_ev, n_od, std::integral_constant<int, mm - NF>{});
+      }
+      const bf16x8 fa = fr[m & 7];
+      // dP^T and S^T are kept in vector registers, the Q / dO fragments in accumulation registers (opaque MFMAs, see
+      // bwd_dkv_pipe_kernel); dP^T is first read three mini-steps after its last MFMA, S^T in the next step
+      auto mma = [&](auto u_c) __attribute__((always_inline)) {
+        constexpr int u = decltype(u_c)::value;
+        const bf16x8& a_ = fa;  // (named references: variables used only inside an asm statement are not captured)
+        if constexpr (m < DK) {
+          f32x16& d_ = dp[u];
+          const bf16x8& b_ = gf[u][m];
+          if (m == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d_) : "v"(a_), "a"(b_));
+          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d_) : "v"(a_), "a"(b_));
+        } else if constexpr (m < 2 * DK) {
+          constexpr int ks = m - DK;
+          f32x16& d_ = nxt[u];
+          const bf16x8& b_ = qf[u][ks];
+          if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d_) : "v"(a_), "a"(b_));
+          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d_) : "v"(a_), "a"(b_));
+        } else {
+          constexpr int ks = (m - 2 * DK) / DB, db = (m - 2 * DK) % DB;
+          dq[u][db] = mfma32(fa, f_old[u][ks], dq[u][db]);
+        }
+      };
+      constexpr std::integral_constant<int, 0> c0{};
+      constexpr std::integral_constant<int, 1> c1{};
+      // exponentials: pair m in mini-step m (m < 16); dS: pairs 0 .. 11 in mini-steps 10 .. 21, then two per mini-step
+      mma(c0);
+      if constexpr (m < 16) exp_half(m_c, c0);
+      if constexpr (m >= 10 && m < 22) ds_pair(std::integral_constant<int, m - 10>{});
+      if constexpr (m >= 22) ds_pair(std::integral_constant<int, 12 + 2 * (m - 22)>{});
+      __builtin_amdgcn_sched_barrier(0);
+      mma(c1);
+      if constexpr (m < 16) exp_half(m_c, c1);
+      if constexpr (m >= 3 && m < 3 + 2 * PER && ((m - 3) & 1) == 0) dma_piece((m - 3) >> 1);
+      if constexpr (m >= 22) ds_pair(std::integral_constant<int, 13 + 2 * (m - 22)>{});
+      if constexpr (m == 12) {  // bookkeeping for the next step (this step's copies have been issued)
+        dma_advance();
+        sV = sK;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        u32x4 v = {pw[u][4 * ks], pw[u][4 * ks + 1], pw[u][4 * ks + 2], pw[u][4 * ks + 3]};
+        f_new[u][ks] = __builtin_bit_cast(bf16x8, v);
+      }
+    // stage t + 2 must have landed; the copies of the DIST - 1 stages after it may still be in flight
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * PER) : "memory");
+    wg_barrier();
+  };
+
+  // Steps are taken two at a time (the two S^T buffers and the two dS^T buffers swap roles without a copy): first the
+  // pairs whose tiles every row of the wave sees completely, then the rest with the mask, up to step nt (whose only
+  // real work is the dQ^T product of the last tile); a pair may run one step past that, which contributes nothing.
+  const int t_full = min(nt, (it.n0 + min(row0[0], row0[1])) / BN) & ~1;
+  int t = 0;
+  for (; t < t_full; t += 2) {
+    step(t, x[0], x[1], f[0], f[1], std::false_type{});
+    step(t + 1, x[1], x[0], f[1], f[0], std::false_type{});
+  }
+  for (; t <= nt; t += 2) {
+    step(t, x[0], x[1], f[0], f[1], std::true_type{});
+    step(t + 1, x[1], x[0], f[1], f[0], std::true_type{});
+  }
+
+  // ---- epilogue: dQ = scale * dQ^T ----
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int r = row0[u] + l32;
+    if (r < it.q_rows) {
+      __bf16* op = p.dq + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head[u] * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const bf16x4 v = pack4(dq[u][db][4 * g] * p.scale, dq[u][db][4 * g + 1] * p.scale, dq[u][db][4 * g + 2] * p.scale,
+                                 dq[u][db][4 * g + 3] * p.scale);
+          *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * g + 4 * hh) = v;
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
@@ -1136,7 +1469,9 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
                        P.q_tiles, d->total_q, d->num_q_heads, lse2p, dsp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  if ((e = launch_transpose(a.k, d->num_kv_heads, D, 32, kjobs, (int)P.kjobs.size(), P.kv32_tiles, kt, stream)) != hipSuccess) return e;
+  if constexpr (D != 128) {  // the head_dim 128 dQ kernel reads K^T from its K tiles
+    if ((e = launch_transpose(a.k, d->num_kv_heads, D, 32, kjobs, (int)P.kjobs.size(), P.kv32_tiles, kt, stream)) != hipSuccess) return e;
+  }
 
   if (!a.accumulate) {  // rows no segment covers receive no gradient
     for (const auto& gap : uncovered_kv_ranges(d)) {
@@ -1158,13 +1493,19 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.heads_per_wg = heads_per_wg(group, dq_waves(D)); p.head_splits = group / p.heads_per_wg;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
-    const size_t smem = (size_t)9 * 32 * D * 2;  // 3 stages of K, V and K^T tiles
     static bool attr = false;
-    constexpr int DQW = D == 128 ? 8 : 4;
-    if ((e = set_smem(&bwd_dq_kernel<D, DQW>, smem, &attr)) != hipSuccess) return e;
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((bwd_dq_kernel<D, DQW>), dim3((unsigned)blocks), dim3(DQW * 64), smem, stream, p);
+    if constexpr (D == 128) {
+      const size_t smem = (size_t)2 * 6 * 32 * D * 2;  // 6 ring slots of a K and a V tile
+      if ((e = set_smem(&bwd_dq_pipe_kernel<D>, smem, &attr)) != hipSuccess) return e;
+      hipLaunchKernelGGL((bwd_dq_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    } else {
+      const size_t smem = (size_t)9 * 32 * D * 2;  // 3 stages of K, V and K^T tiles
+      constexpr int DQW = 4;
+      if ((e = set_smem(&bwd_dq_kernel<D, DQW>, smem, &attr)) != hipSuccess) return e;
+      hipLaunchKernelGGL((bwd_dq_kernel<D, DQW>), dim3((unsigned)blocks), dim3(DQW * 64), smem, stream, p);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {  // dK, dV
