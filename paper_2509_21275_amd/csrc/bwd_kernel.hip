@@ -319,8 +319,6 @@ struct DkvParams {
   int32_t accumulate;
 };
 
-// element offset of (row r, 16-byte chunk c) in a 32-row chunk-major tile
-__device__ __forceinline__ int cm_elem(int r, int c) { return (c * 32 + (r ^ ((c & 3) << 2))) * 8; }
 
 template <int D, int KB>  // KB: 32-key blocks per workgroup (2 KB waves)
 __global__ __launch_bounds__(KB * 128, 4 / KB) void bwd_dkv_kernel(DkvParams p) {
@@ -608,44 +606,6 @@ __global__ __launch_bounds__(KB * 128, 4 / KB) void bwd_dkv_kernel(DkvParams p) 
           *op = pack4(v0, v1, v2, v3);
         }
     }
-  }
-}
-
-// LDS accesses as opaque instructions, for bwd_dkv_pipe_kernel.  The compiler makes a wave wait for ALL of its
-// outstanding global->LDS copies before an LDS read it cannot tell apart from their destinations (the
-// transpose read in particular), which would serialise the copies of later stages with the reads of the
-// current one.  Issued like this, the reads are invisible to that logic; the kernel orders them itself with
-// explicit s_waitcnt lgkmcnt(n) (LDS operations of a wave complete in order).  `addr` is a byte address.
-template <int OFF>
-__device__ __forceinline__ bf16x8 lds_asm_read16(unsigned addr) {
-  bf16x8 v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
-  return v;
-}
-template <int OFF>
-__device__ __forceinline__ f32x4 lds_asm_read16f(unsigned addr) {
-  f32x4 v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
-  return v;
-}
-template <int OFF>
-__device__ __forceinline__ s16x4 lds_asm_read_tr(unsigned addr) {
-  s16x4 v;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
-  return v;
-}
-template <int OFF>
-__device__ __forceinline__ void lds_asm_write16(unsigned addr, bf16x8 v) {
-  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
-}
-__device__ __forceinline__ unsigned lds_addr(const lds_bf16* p) { return (unsigned)(uintptr_t)p; }
-__device__ __forceinline__ unsigned lds_addr(const lds_f32* p) { return (unsigned)(uintptr_t)p; }
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
   }
 }
 
@@ -1574,7 +1534,9 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   P.lse2p_off = P.blob_bytes;
   P.dsp_off = P.lse2p_off + up256(row_slots * sizeof(float));
   P.kt_off = P.dsp_off + up256(row_slots * sizeof(float));
-  P.total = P.kt_off + up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16));
+  // transposed K images only for head_dim 64 (the head_dim 128 dQ kernel reads K^T from its K tiles)
+  // (256 bytes remain in any case: the dK/dV kernels copy the LSE / D rows 64 at a time, up to 32 past a segment's last)
+  P.total = P.kt_off + (d->head_dim == 128 ? 256 : up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16)));
 }
 
 std::vector<char> bwd_blob(const BwdPlan& P) {

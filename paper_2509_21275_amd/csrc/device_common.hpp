@@ -31,17 +31,8 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// Element i of an accumulator tile that lives in accumulation registers (kernels that use more than 256
-// registers per lane keep every MFMA result there), read with one opaque register move.  A plain read would
-// give the register allocator a vector-register use of the tile, and it then keeps a vector-register copy of
-// the whole tile alive across the main loop.  The move is also ordered against other opaque statements and
-// scheduling fences, which pins the arithmetic that depends on it.  The caller guarantees the distance to the
-// MFMA that wrote the register (mfma_settle() after the last MFMA, or enough instructions in between).
-__device__ __forceinline__ float read_acc_elem(const f32x16& acc, int i) {
-  float e = acc[i], t;
-  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(e));
-  return t;
-}
+// Idles long enough for the last MFMA's results to be written back (for code that reads results of MFMAs the
+// compiler does not know about).
 __device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
 
 // value of the lane 32 away
@@ -77,20 +68,6 @@ __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) 
 // for e = 0..3, 16-bit element (i % 4) of the 8 bytes addressed by lane (i / 4 + 4 e) of the group.
 __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
-}
-
-// A operand (32 rows x 16 k) in C-order taken from a row-major LDS tile T[k][m] (k = contraction index
-// along LDS rows, m = operand row along LDS columns): returns T[k0 + 8 (e/4) + 4 hh + e%4][m0 + l32], e = 0..7.
-// `stride` is the LDS row pitch in elements.
-__device__ __forceinline__ bf16x8 lds_a_operand_transposed(const __bf16* tile, int stride, int k0, int m0, int lane) {
-  const int hh = lane >> 5;
-  const int row = k0 + 4 * hh + ((lane & 15) >> 2);
-  const int col = m0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const __bf16* p = tile + row * stride + col;
-  s16x4 lo = lds_read_tr(p);
-  s16x4 hi = lds_read_tr(p + 8 * stride);
-  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
 }
 
 }  // namespace chunk_attn

@@ -3,18 +3,19 @@
 // part of their own slice; packed sequences see nothing of each other).
 //
 // A workgroup takes one forward work item -- a tile of query rows of one segment -- for the query heads of
-// one group that share a key/value head, and streams that segment's visible keys/values through LDS in
-// tiles of 64 rows: K row-major, V as the pre-transposed image (transpose_kernel.hip), both copied
-// global->LDS without passing through registers and double-buffered.  Scores are computed transposed,
-// S^T = K Q^T, so that after the MFMA every lane holds one query column: row maximum and row sum are a loop
-// over the lane's own registers plus one exchange with the lane 32 away, and the bf16 probabilities are
-// already laid out as the B operand of O^T += V^T P^T (device_common.hpp, "C-order").
+// one group that share a key/value head, and streams that segment's visible keys/values through LDS, copied
+// global->LDS without passing through registers.  Scores are computed transposed, S^T = K Q^T, so that after
+// the MFMA every lane holds one query column: row maximum and row sum are a loop over the lane's own
+// registers plus one exchange with the lane 32 away, and the bf16 probabilities are already laid out as the
+// B operand of O^T += V^T P^T (device_common.hpp, "C-order").
 //
 // Two kernels:
 //   fwd_kernel       online softmax with a lazily moved reference maximum, one 32-row query block per wave,
-//                    two waves per SIMD.  Used for head_dim 64, and for head_dim 128 as the second pass below.
-//   fwd_pipe_kernel  head_dim 128: one wave per SIMD with 64 query rows, software pipelined over the key
-//                    tiles, reference maximum fixed by the first tile; rows whose scores outgrow it are
+//                    two waves per SIMD, tiles of 64 keys (K row-major, V as the pre-transposed image of
+//                    transpose_kernel.hip, double-buffered).  Used for head_dim 64, and for head_dim 128 as the
+//                    second pass below.
+//   fwd_pipe_kernel  head_dim 128: one wave per SIMD with 64 query rows, software pipelined over stages of 32
+//                    keys, reference maximum fixed by the first stage; rows whose scores outgrow it are
 //                    flagged and recomputed by fwd_kernel, launched right after over the flagged items only.
 #include <type_traits>
 
@@ -261,32 +262,43 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void fwd_kernel(FwdParams p)
 }
 
 // ------------------------------------------------------------------------------------------------
-// Pipelined forward for head_dim 128: one wave per SIMD, 64 query rows per wave.
+// Pipelined forward for head_dim 128: one wave per SIMD, 64 query rows per wave (two 32-row "units"), keys
+// streamed in stages of 32.
 //
-// Every K and V^T fragment read from LDS feeds two MFMAs (the wave's two 32-row query blocks), which halves
-// the LDS traffic per MFMA.  That needs more than 256 registers per lane, so only one wave fits a SIMD and
-// the overlap of matrix and vector work has to come from inside the wave: the loop is software pipelined.
-// Iteration t runs   O^T += V^T(t-1) P^T(t-1)   next to the mask / row maximum of S^T(t), and
-//                    S^T(t+1) = K(t+1) Q^T      next to the exponentials / row sums of S^T(t),
-// matrix and vector instructions of each pair being independent.  The accumulators stay in accumulation
-// registers for the whole loop (the rare rescale and the epilogue read them through opaque single-register
-// moves, see device_common.hpp); the loop has one body for both LDS buffers (addresses toggled by XOR).
+// A wave issues at most one instruction every four cycles and an MFMA holds the matrix pipe for 32, so the loop
+// is laid out instruction by instruction.  In step t a wave runs
+//     O^T += V(t-1)^T P^T(t-1)        S^T(t+1) = K(t+1) Q^T        (matrix pipe)
+//     P^T(t) = exp2(S^T(t) c - m c) and its row sums                (vector pipe)
+// as 16 mini-steps of one LDS operand fragment and the two MFMAs it feeds (one per unit), each MFMA followed by
+// the vector work of one score.  K and V tiles are copied global->LDS into a ring of DIST + 3 slots, stored
+// chunk-major; V^T is read from the V tile itself with the LDS transpose read.  Fragments are fetched four
+// mini-steps ahead with opaque LDS reads and explicit lgkmcnt waits; S^T lives in vector registers, where the
+// vector work reads it directly, the Q fragments and O^T in accumulation registers (tiles.hpp).
+// The reference maximum of the softmax is fixed by the first stage, so O^T is never rescaled in the loop; a row
+// whose later scores outgrow it raises the workgroup's redo flag and the item is recomputed by fwd_kernel.
+// Steps whose stage needs the causal mask (the last few of the walk) or lies past the end run a second variant of
+// the step that masks in the vector work.
 // ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
-  constexpr int WAVES = 4, QB = 2;
-  constexpr int NT = WAVES * 64;
-  constexpr int BN = 64;       // key rows per LDS tile
-  constexpr int KC = D / 8;    // 16-byte chunks per K row
+  constexpr int NW = 4;        // waves
+  constexpr int BN = 32;       // key rows per stage
+  constexpr int KC = D / 8;    // 16-byte chunks per K / V row
   constexpr int DK = D / 16;   // k-steps of S^T = K Q^T
   constexpr int DB = D / 32;   // 32-row blocks of O^T
-  constexpr int KT = BN * D;   // elements per K tile and per V^T image
-  constexpr int WR = 32 * QB;  // query rows per wave
-  static_assert((KT & (KT - 1)) == 0, "buffer pitch must be a power of two");
+  constexpr int KT = BN * D;   // elements per tile
+  constexpr int DIST = 3;      // stages copied ahead
+  constexpr int NS = DIST + 3; // ring slots: stages t - 1 .. t + 1 in use, t + 2 .. t + 1 + DIST on their way
+  constexpr int NF = 2 * DB + DK;      // operand fragments (mini-steps) per step: V^T, then K rows
+  constexpr int AHEAD = 4;             // fragments in flight
+  constexpr int NP = BN * KC / 64;     // 64-slot pieces per tile
+  constexpr int PER = 2 * NP / NW;     // global->LDS copies per wave and stage
+  static_assert(D == 128 && NF == 16 && PER == 4, "the mini-step schedule below is written for head_dim 128");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  __bf16* Ks = reinterpret_cast<__bf16*>(smem);  // [2][BN][D]  swizzled rows
-  __bf16* Vs = Ks + 2 * KT;                      // [2][D][BN]  transposed image
+  lds_bf16* const L = (lds_bf16*)smem;
+  constexpr int K_OFF = 0;               // [NS][KT]  K rows of stage n in slot n % NS (chunk-major)
+  constexpr int V_OFF = K_OFF + NS * KT; // [NS][KT]  V rows
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -297,242 +309,286 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
   const FwdItem it = p.items[blockIdx.x / inner_n];
   const int kvh = inner % p.num_kv_heads, hs = inner / p.num_kv_heads;
   const int head = kvh * p.group + hs * p.heads_per_wg + wave % p.heads_per_wg;
-  const int wave_row0 = (wave / p.heads_per_wg) * WR;
+  const int wave_row0 = (wave / p.heads_per_wg) * 64;  // the wave's units are rows wave_row0 + 32 u .. + 31 of `head`
 
-  const int n_wg = it.n0 + it.q_rows - 1;  // keys visible to the last valid row
-  const int nt = (n_wg + BN - 1) / BN;     // every wave runs all tiles of the workgroup (masked ones give P = 0)
+  const int n_wg = it.n0 + it.q_rows - 1;    // keys visible to the last valid row
+  const int nt = (n_wg + BN - 1) / BN;       // stages
 
   const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
   const __bf16* __restrict__ Kg = p.k + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
-  const __bf16* __restrict__ Vimg = p.vt + ((int64_t)kvh * p.total_kv_tiles + it.kv_tile0) * KT;
+  const __bf16* __restrict__ Vg = p.v + (int64_t)it.kv_row0 * kv_stride + (int64_t)kvh * D;
 
-  constexpr int NK = BN * KC / NT, NV = KT / 8 / NT;
-  int k_chunk[NK], k_row[NK];  // element offset of the lane's chunk inside its row, and the row
-#pragma unroll
-  for (int i = 0; i < NK; ++i) {
-    const int x = (i * WAVES + wave) * 64 + lane;
-    k_row[i] = x / KC;
-    k_chunk[i] = unswz<KC>(k_row[i], x % KC) * 8;
-  }
-  // branch-free (the loop body must stay one basic block): rows past the last key repeat it
-  auto dma_k = [&](int t, int buf) {
-    const __bf16* ksrc = Kg + (int64_t)(BN * t) * kv_stride;  // wave-uniform
-    const int last_row = n_wg - 1 - BN * t;
-    __bf16* kdst = Ks + buf * KT;
-#pragma unroll
-    for (int i = 0; i < NK; ++i)
-      dma16(ksrc + (unsigned)(min(k_row[i], last_row) * (int)kv_stride + k_chunk[i]), kdst + (i * WAVES + wave) * 512);
-  };
-  auto dma_v = [&](int t, int buf) {
-    const __bf16* vsrc = Vimg + (int64_t)t * KT;  // wave-uniform
-    __bf16* vdst = Vs + buf * KT;
-#pragma unroll
-    for (int i = 0; i < NV; ++i)
-      dma16(vsrc + (unsigned)(((i * WAVES + wave) * 64 + lane) * 8), vdst + (i * WAVES + wave) * 512);
-  };
-
-  dma_k(0, 0);
-  if (nt > 1) dma_k(1, 1);
-  // the first iteration multiplies P = 0 with "V^T(-1)": give it zeros rather than whatever LDS holds
+  // the ring slots the prologue does not fill are read before anything is copied into them (V(-1) in step 0)
   {
     bf16x8 z;
 #pragma unroll
     for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.0f;
-#pragma unroll
-    for (int i = 0; i < KT / 8 / NT; ++i) *reinterpret_cast<bf16x8*>(Vs + KT + (i * NT + tid) * 8) = z;
+    for (int x = tid; x < (NS - DIST - 1) * KT / 8; x += NW * 64) {
+      lds_store8(L + K_OFF + (DIST + 1) * KT + x * 8, z);
+      lds_store8(L + V_OFF + (DIST + 1) * KT + x * 8, z);
+    }
   }
 
-  // Q fragments: B operand of S^T = K Q^T; lane holds Q[row = 32 qb + l32][16 ks + 8 hh ..+7]
-  bf16x8 qf[QB][DK];
+  // Q fragments (B operands of S^T = K Q^T): lane holds Q[row = l32 of the unit][16 ks + 8 hh ..+7]
+  bf16x8 qf[2][DK];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int r = min(wave_row0 + 32 * qb + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
+  for (int u = 0; u < 2; ++u) {
+    const int r = min(wave_row0 + 32 * u + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
     const __bf16* qp = p.q + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < DK; ++ks) qf[u][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
 
+  // ---- staging: the 2 NP pieces of a stage (NP of K, then NP of V) are dealt to the waves round robin; a piece is
+  // 64 consecutive slots of a chunk-major tile = two chunk columns of 32 rows.  Past the last stage the last one is
+  // copied again. ----
+  unsigned v_full[PER], v_last[PER];  // byte offset of the lane's chunk from the tile's first row: full tile, last tile
+  {
+    const int last_row = n_wg - 1 - (nt - 1) * BN;  // rows past the last key repeat it (masked)
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int x = ((i * NW + wave) % NP) * 64 + lane;
+      const int off = (x >> 5) * 8, row = (x & 31) ^ (((x >> 5) & 3) << 2);
+      v_full[i] = (unsigned)(row * (int)kv_stride + off) * 2u;
+      v_last[i] = (unsigned)(min(row, last_row) * (int)kv_stride + off) * 2u;
+    }
+  }
+  int d_t = 0, d_slot = 0;   // stage to copy next (clamped to the last one) and its slot
+  int64_t d_off = 0;         // element offset of its first row
+  auto dma_piece = [&](int i) __attribute__((always_inline)) {
+    const int piece = i * NW + wave;  // wave-uniform; i < NP / NW: a piece of K, else of V
+    const unsigned voff = d_t == nt - 1 ? v_last[i] : v_full[i];
+    const char* base = reinterpret_cast<const char*>((i < NP / NW ? Kg : Vg) + d_off);
+    lds_bf16* dst = L + (i < NP / NW ? K_OFF + piece * 512 : V_OFF + (piece - NP) * 512) + d_slot * KT;
+    dma16(base + voff, dst);
+  };
+  auto dma_advance = [&]() __attribute__((always_inline)) {
+    if (d_t + 1 < nt) {
+      ++d_t;
+      d_off += BN * kv_stride;
+    }
+    d_slot = d_slot == NS - 1 ? 0 : d_slot + 1;
+  };
+
+  // per-lane operand addresses inside a tile
+  int x_off[2], t_off[2];
+#pragma unroll
+  for (int par = 0; par < 2; ++par) x_off[par] = cm_elem(l32, 2 * par + hh);
+  {
+    const int j = lane & 15, grp = (lane >> 4) & 1;
+    const int cl = 2 * grp + ((j & 3) >> 1);
+    const int r0 = 4 * hh + (j >> 2);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) t_off[half] = cm_elem(r0 + 8 * half, cl) + 4 * (j & 1);
+  }
+  const unsigned k_ev0 = lds_addr(L + K_OFF + x_off[0]), k_od0 = lds_addr(L + K_OFF + x_off[1]);
+  const unsigned t_lo0 = lds_addr(L + V_OFF + t_off[0]), t_hi0 = lds_addr(L + V_OFF + t_off[1]);
+  constexpr unsigned SLOT = KT * 2;  // bytes per ring slot
+  auto load_rows = [&](unsigned ev_addr, unsigned od_addr, auto ks_c) __attribute__((always_inline)) {
+    constexpr int ks = decltype(ks_c)::value;
+    constexpr int off = (ks >> 1) * (4 * 32 * 8) * 2;
+    return lds_asm_read16<off>((ks & 1) ? od_addr : ev_addr);
+  };
+  auto load_t = [&](unsigned lo_addr, unsigned hi_addr, auto m_c) __attribute__((always_inline)) {
+    constexpr int m = decltype(m_c)::value;  // ks2 * DB + db
+    constexpr int off = ((m / DB) * (16 * 8) + (m % DB) * (4 * 32 * 8)) * 2;
+    const s16x4 lo = lds_asm_read_tr<off>(lo_addr);
+    const s16x4 hi = lds_asm_read_tr<off>(hi_addr);
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  // A wait the compiler can see for the loads above, before the first copy is issued: it then has no reason to put
+  // full waits for outstanding loads into the loop.
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  // prologue: stages 0 .. DIST; stages 0 and 1 must have landed before the first step
+#pragma unroll
+  for (int s = 0; s <= DIST; ++s) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) dma_piece(i);
+    dma_advance();
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * PER) : "memory");
+  wg_barrier();
+
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  f32x16 oacc[QB][DB];
+  f32x16 oacc[2][DB];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
+  for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int db = 0; db < DB; ++db) oacc[qb][db] = zero16;
-  float m_run[QB], l_run[QB];
+    for (int db = 0; db < DB; ++db) oacc[u][db] = zero16;
+  f32x16 x[2][2];      // S^T: [buffer][unit]
+  bf16x8 f[2][2][2];   // P^T as B operands: [buffer][unit][k-step]
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { m_run[qb] = 0.f; l_run[qb] = 0.f; }
-  bool risk = false;
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[b][u][ks][i] = (__bf16)0.0f;
   const float c = p.scale_log2;
+  bf16x8 fr[8];  // ring of operand fragments
 
-  // LDS operand addresses (elements); k_off addresses the K buffer of tile t + 1, v_off the V^T buffer of tile t - 1
-  int k_off[DK], v_off[4];
+  // S^T(0) = K(0) Q^T and the reference maximum of each row; then the first fragments of step 0 (zeros)
+  float mc[2], l_run[2];
+  {
+    bf16x8 a[DK];
+    static_for<0, DK>([&](auto ks_c) __attribute__((always_inline)) { a[decltype(ks_c)::value] = load_rows(k_ev0, k_od0, ks_c); });
+    {
+      const unsigned sT = (NS - 1) * SLOT;
+      static_for<0, AHEAD>([&](auto m_c) __attribute__((always_inline)) { fr[decltype(m_c)::value] = load_t(t_lo0 + sT, t_hi0 + sT, m_c); });
+    }
+    asm volatile("s_waitcnt lgkmcnt(%8)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]) : "n"(2 * AHEAD));
 #pragma unroll
-  for (int ks = 0; ks < DK; ++ks) k_off[ks] = tile_elem<KC>(l32, 2 * ks + hh);
+    for (int ks = 0; ks < DK; ++ks)
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) v_off[ks] = tile_elem<8>(l32, 2 * ks + hh) + KT;
-
+      for (int u = 0; u < 2; ++u) {
+        f32x16& d_ = x[0][u];
+        const bf16x8& b_ = qf[u][ks];
+        if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d_) : "v"(a[ks]), "a"(b_));
+        else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d_) : "v"(a[ks]), "a"(b_));
+      }
+    mfma_settle();
+    asm volatile("s_nop 15" : "+v"(x[0][0]), "+v"(x[0][1]));  // the reads below come after the MFMAs have written
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int lim = it.n0 + wave_row0 + 32 * u + l32;  // stage 0: visible iff local key index < lim (>= 1)
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int j = 8 * (i >> 2) + 4 * hh + (i & 3);
+        if (j < lim) mx = fmaxf(mx, x[0][u][i]);
+      }
+      mc[u] = max_halves(mx) * c;
+      l_run[u] = 0.f;
+    }
+  }
+  bool risk = false;
+  const float big = __builtin_amdgcn_exp2f(p.ref_limit);
   bf16x2 ones;
   ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
 
-  // S^T = K Q^T of one tile: [64 keys] x [64 queries], dst[qb][kb].  Two score tiles live in the accumulation
-  // registers: the one being computed (next tile) and the one whose exponentials are being taken.
-  f32x16 s[2][QB][2];
-  auto qk = [&](f32x16 (&dst)[QB][2]) {
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Ks + k_off[ks]);
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Ks + k_off[ks] + 32 * D);
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        dst[qb][0] = mfma32(a0, qf[qb][ks], ks == 0 ? zero16 : dst[qb][0]);
-        dst[qb][1] = mfma32(a1, qf[qb][ks], ks == 0 ? zero16 : dst[qb][1]);
-      }
-    }
+  // In program order mini-step m reads fragment m + 4: two instructions for the transposed fragments (0 .. 7 of this
+  // step, 0 .. 3 of the next), one for the rows fragments (8 .. 15).  lgkm_wait(m) = number of LDS instructions between
+  // the read of fragment m and the start of mini-step m, where the wait stands.
+  auto lgkm_wait = [](int m) {
+    constexpr int tab[16] = {6, 6, 6, 6, 6, 5, 4, 3, 3, 3, 3, 3, 3, 4, 5, 6};
+    return tab[m];
   };
-  bf16x8 pf[QB][4];  // P^T of the previous tile (B operands)
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) pf[qb][j][i] = (__bf16)0.0f;
-  auto pv = [&]() {
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vs + v_off[ks] + db * 32 * 64);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = mfma32(a, pf[qb][ks], oacc[qb][db]);
-      }
-  };
-
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  qk(s[0]);  // S^T(0)
-#pragma unroll
-  for (int ks = 0; ks < DK; ++ks) k_off[ks] ^= KT;
-  // The reference maximum only has to keep exp2 in range, so it is fixed by the first tile and never moved:
-  // O^T is never rescaled and stays in the accumulation registers.  Should a later tile's probabilities
-  // exceed 2^ref_limit, the workgroup raises its redo flag and the item is recomputed by the rescaling
-  // kernel (fwd_kernel) launched right after this one.
-  mfma_settle();
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int lim = it.n0 + wave_row0 + 32 * qb + l32;  // tile 0: visible iff local key index < lim (>= 1)
-    float mx = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int j = 8 * (i >> 2) + 4 * hh + (i & 3);
-      const float a0 = read_acc_elem(s[0][qb][0], i), a1 = read_acc_elem(s[0][qb][1], i);
-      if (j < lim) mx = fmaxf(mx, a0);
-      if (j + 32 < lim) mx = fmaxf(mx, a1);
-    }
-    m_run[qb] = max_halves(mx);
-  }
-  const float big = __builtin_amdgcn_exp2f(p.ref_limit);
-  __syncthreads();  // every wave has read K(0): its buffer may be refilled
-
-  // One tile: O^T += V^T(t-1) P^T(t-1) and S^T(t+1) = K(t+1) Q^T (matrix pipe) next to P^T(t) = exp2(S^T(t) c - m c)
-  // and its row sums (vector pipe).  cur holds S^T(t), nxt receives S^T(t+1).  The tile is cut into 32 steps
-  // of one LDS operand fragment, the two MFMAs it feeds and the exponentials of two scores; every step also
-  // issues the fragment read of the step four ahead (with one wave per SIMD nothing else would cover the LDS
-  // latency).  Scheduling fences keep the steps apart, so that vector work is spread evenly under the MFMAs.
-  auto tile = [&](int t, f32x16 (&cur)[QB][2], f32x16 (&nxt)[QB][2], auto masked_c) {
+  int sV = 0;  // slot of stage t
+  auto step = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2], bf16x8 (&f_old)[2][2], bf16x8 (&f_new)[2][2],
+                  auto masked_c) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_c)::value;
-    constexpr int AHEAD = 4;
-    dma_k(min(t + 2, nt - 1), t & 1);  // past the end: the last tile again, into a buffer nobody reads
-    dma_v(min(t, nt - 1), t & 1);
-    bf16x8 fr[8];  // ring of operand fragments
-    auto load_frag = [&](int m) {
-      if (m < 16) return *reinterpret_cast<const bf16x8*>(Vs + v_off[m >> 2] + (m & 3) * 32 * 64);  // V^T(t-1): k-step, block
-      const int mm = m - 16;                                                                          // K(t+1): k-step, key half
-      return *reinterpret_cast<const bf16x8*>(Ks + k_off[mm >> 1] + (mm & 1) * 32 * D);
+    const int sK = sV == NS - 1 ? 0 : sV + 1;   // stage t + 1
+    const int sM = sV == 0 ? NS - 1 : sV - 1;   // stage t - 1
+    const unsigned k_ev = k_ev0 + sK * SLOT, k_od = k_od0 + sK * SLOT;
+    const unsigned t_lo = t_lo0 + sM * SLOT, t_hi = t_hi0 + sM * SLOT, n_lo = t_lo0 + sV * SLOT, n_hi = t_hi0 + sV * SLOT;
+    // MASKED: element i (key 8 (i / 4) + 4 hh + i % 4 of the stage) of unit u is visible iff 8 (i / 4) + i % 4 < lim[u]
+    int lim[2];
+    if (MASKED) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) lim[u] = t < nt ? it.n0 + wave_row0 + 32 * u + l32 - BN * t - 4 * hh : -0x40000000;
+    }
+    unsigned pw[2][8];  // P^T(t), packed pairs
+    float ps[2] = {0.f, 0.f};
+    float e_hold[2];
+    // vector work of score 2 dw + q of unit u (pair j = 8 u + dw), pinned to where it is written; a pair is converted
+    // one mini-step after its exponentials (a transcendental result cannot be consumed by the very next instruction)
+    auto finish_pair = [&](int jp) __attribute__((always_inline)) {
+      bf16x2 w;
+      w[0] = (__bf16)e_hold[0]; w[1] = (__bf16)e_hold[1];
+      ps[jp >> 3] = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps[jp >> 3], false);
+      unsigned wu = __builtin_bit_cast(unsigned, w);
+      asm volatile("" : "+v"(wu));
+      pw[jp >> 3][jp & 7] = wu;
     };
-    unsigned pw[QB][16];  // P^T(t) as packed pairs
-    float ps[QB][2];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) ps[qb][0] = ps[qb][1] = 0.f;
-#pragma unroll
-    for (int m = 0; m < AHEAD; ++m) fr[m] = load_frag(m);
-    // the last MFMA that wrote `cur` is far behind (end of the previous tile, a barrier and the copy set-up lie
-    // between); the nop makes the required distance to the opaque reads explicit
-    asm volatile("s_nop 15" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int m = 0; m < 32; ++m) {
-      if (m + AHEAD < 32) fr[(m + AHEAD) & 7] = load_frag(m + AHEAD);
-      const bf16x8 f = fr[m & 7];
-      if (m < 16) {
-        const int ks = m >> 2, db = m & 3;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = mfma32(f, pf[qb][ks], oacc[qb][db]);
-      } else {
-        const int ks = (m - 16) >> 1, kb = (m - 16) & 1;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) nxt[qb][kb] = mfma32(f, qf[qb][ks], ks == 0 ? zero16 : nxt[qb][kb]);
+    auto vec_half = [&](auto j_c, auto q_c) __attribute__((always_inline)) {
+      constexpr int j = decltype(j_c)::value, q = decltype(q_c)::value;
+      constexpr int u = j >> 3, i = 2 * (j & 7) + q;
+      if constexpr (j > 0 && q == 0) finish_pair(j - 1);
+      float tt = cur[u][i] * c - mc[u];
+      if (MASKED) {
+        if (8 * (i >> 2) + (i & 3) >= lim[u]) tt = -INFINITY;
       }
-      {  // scores 2 dw, 2 dw + 1 of block (qb, kb): exponentials, packed pair, row sum
-        const int qb = m >> 4, kb = (m >> 3) & 1, dw = m & 7;
-        const float mc = m_run[qb] * c;
-        const int lim = it.n0 + wave_row0 + 32 * qb + l32 - BN * t;  // visible iff local key index < lim
-        // opaque (ordered) reads of the scores, and the result pinned before the step's fence: otherwise the
-        // compiler gathers the vector work of the whole tile in one place
-        float e0 = __builtin_amdgcn_exp2f(read_acc_elem(cur[qb][kb], 2 * dw) * c - mc);
-        float e1 = __builtin_amdgcn_exp2f(read_acc_elem(cur[qb][kb], 2 * dw + 1) * c - mc);
-        if (MASKED) {
-          const int j = 32 * kb + 8 * (dw >> 1) + 4 * hh + 2 * (dw & 1);
-          if (j >= lim) e0 = 0.f;
-          if (j + 1 >= lim) e1 = 0.f;
+      e_hold[q] = __builtin_amdgcn_exp2f(tt);
+      asm volatile("" : "+v"(e_hold[q]));
+    };
+    asm volatile("s_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, NF>([&](auto m_c) __attribute__((always_inline)) {
+      constexpr int m = decltype(m_c)::value;
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(fr[m & 7]) : "n"(lgkm_wait(m)));
+      {  // read the fragment of mini-step m + AHEAD (past the end: the next step's first transposed fragments)
+        constexpr int mm = m + AHEAD;
+        if constexpr (mm < 2 * DB) fr[mm & 7] = load_t(t_lo, t_hi, std::integral_constant<int, mm>{});
+        else if constexpr (mm < NF) fr[mm & 7] = load_rows(k_ev, k_od, std::integral_constant<int, mm - 2 * DB>{});
+        else fr[mm & 7] = load_t(n_lo, n_hi, std::integral_constant<int, mm - NF>{});
+      }
+      const bf16x8 fa = fr[m & 7];
+      auto mma = [&](auto u_c) __attribute__((always_inline)) {
+        constexpr int u = decltype(u_c)::value;
+        if constexpr (m < 2 * DB) {
+          constexpr int ks = m / DB, db = m % DB;
+          oacc[u][db] = mfma32(fa, f_old[u][ks], oacc[u][db]);
+        } else {
+          constexpr int ks = m - 2 * DB;
+          const bf16x8& a_ = fa;  // (named references: variables used only inside an asm statement are not captured)
+          f32x16& d_ = nxt[u];
+          const bf16x8& b_ = qf[u][ks];
+          if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d_) : "v"(a_), "a"(b_));
+          else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d_) : "v"(a_), "a"(b_));
         }
-        bf16x2 w;
-        w[0] = (__bf16)e0; w[1] = (__bf16)e1;
-        ps[qb][dw & 1] = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps[qb][dw & 1], false);
-        unsigned wu = __builtin_bit_cast(unsigned, w);
-        asm volatile("" : "+v"(wu));
-        pw[qb][8 * kb + dw] = wu;
+      };
+      constexpr std::integral_constant<int, 0> c0{};
+      constexpr std::integral_constant<int, 1> c1{};
+      mma(c0);
+      vec_half(m_c, c0);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(c1);
+      vec_half(m_c, c1);
+      if constexpr (m >= 3 && m < 3 + 2 * PER && ((m - 3) & 1) == 0) dma_piece((m - 3) >> 1);
+      if constexpr (m == 12) {  // bookkeeping for the next step (this step's copies have been issued)
+        dma_advance();
+        sV = sK;
       }
       __builtin_amdgcn_sched_barrier(0);
-    }
+    });
+    finish_pair(15);
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      const float sum = ps[qb][0] + ps[qb][1];
-      risk |= !(sum < big);
-      l_run[qb] += sum;
+    for (int u = 0; u < 2; ++u) {
+      risk |= !(ps[u] < big);
+      l_run[u] += ps[u];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u32x4 v = {pw[qb][4 * j], pw[qb][4 * j + 1], pw[qb][4 * j + 2], pw[qb][4 * j + 3]};
-        pf[qb][j] = __builtin_bit_cast(bf16x8, v);
+      for (int ks = 0; ks < 2; ++ks) {
+        u32x4 v = {pw[u][4 * ks], pw[u][4 * ks + 1], pw[u][4 * ks + 2], pw[u][4 * ks + 3]};
+        f_new[u][ks] = __builtin_bit_cast(bf16x8, v);
       }
     }
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) k_off[ks] ^= KT;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) v_off[ks] ^= KT;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    // stage t + 2 must have landed; the copies of the DIST - 1 stages after it may still be in flight
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * PER) : "memory");
+    wg_barrier();
   };
-  // Tiles are taken two at a time (the two score tiles swap roles without a copy), first the pairs every row
-  // of the wave sees completely, then the ones that need the mask; a pair may run one tile past the end,
-  // which the mask turns into P = 0.  The accumulators never pass through a conditional.
-  const int t_full = min(nt, (it.n0 + wave_row0) / BN) & ~1;  // tiles [0, t_full) are complete for every row
-  for (int t = 0; t < t_full; t += 2) {
-    tile(t, s[0], s[1], std::false_type{});
-    tile(t + 1, s[1], s[0], std::false_type{});
+
+  // Steps are taken two at a time (the two S^T buffers and the two P^T buffers swap roles without a copy): first the
+  // pairs whose stages every row of the wave sees completely, then the rest with the mask, up to step nt (whose only
+  // real work is the O^T product of the last stage); a pair may run one step past that, which contributes nothing.
+  const int t_full = min(nt, (it.n0 + wave_row0) / BN) & ~1;
+  int t = 0;
+  for (; t < t_full; t += 2) {
+    step(t, x[0], x[1], f[0], f[1], std::false_type{});
+    step(t + 1, x[1], x[0], f[1], f[0], std::false_type{});
   }
-  for (int t = t_full; t < nt; t += 2) {
-    tile(t, s[0], s[1], std::true_type{});
-    tile(t + 1, s[1], s[0], std::true_type{});
+  for (; t <= nt; t += 2) {
+    step(t, x[0], x[1], f[0], f[1], std::true_type{});
+    step(t + 1, x[1], x[0], f[1], f[0], std::true_type{});
   }
-  pv();  // O^T += V^T P^T of the last tile
   if (__any(risk) && lane == 0) p.redo[blockIdx.x] = 1;
 
   // ---- epilogue: O = O^T / l, LSE = ln(l) + m scale ----
-  mfma_settle();
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int r = wave_row0 + 32 * qb + l32;
-    const float l_tot = sum_halves(l_run[qb]);
+  for (int u = 0; u < 2; ++u) {
+    const int r = wave_row0 + 32 * u + l32;
+    const float l_tot = sum_halves(l_run[u]);
     if (r < it.q_rows) {
       const float inv = 1.0f / l_tot;
       __bf16* op = p.o + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D;
@@ -540,12 +596,11 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const bf16x4 v = pack4(read_acc_elem(oacc[qb][db], 4 * g) * inv, read_acc_elem(oacc[qb][db], 4 * g + 1) * inv,
-                                 read_acc_elem(oacc[qb][db], 4 * g + 2) * inv, read_acc_elem(oacc[qb][db], 4 * g + 3) * inv);
+          const bf16x4 v = pack4(oacc[u][db][4 * g] * inv, oacc[u][db][4 * g + 1] * inv, oacc[u][db][4 * g + 2] * inv,
+                                 oacc[u][db][4 * g + 3] * inv);
           *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * g + 4 * hh) = v;
         }
-      if (hh == 0)
-        p.lse[(int64_t)head * p.total_q + it.q_row0 + r] = (m_run[qb] * c + log2f(l_tot)) * 0.6931471805599453f;
+      if (hh == 0) p.lse[(int64_t)head * p.total_q + it.q_row0 + r] = (mc[u] + log2f(l_tot)) * 0.6931471805599453f;
     }
   }
 }
@@ -554,7 +609,7 @@ template <int D, int WAVES>
 static hipError_t launch_fwd_t(const FwdParams& p, int num_blocks, hipStream_t stream);
 
 static hipError_t launch_fwd_pipe(const FwdParams& p, int num_blocks, hipStream_t stream) {
-  const size_t smem = (size_t)4 * 64 * 128 * 2;
+  const size_t smem = (size_t)2 * 6 * 32 * 128 * 2;  // 6 ring slots of a K and a V tile
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_pipe_kernel<128>),

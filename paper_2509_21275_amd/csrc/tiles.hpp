@@ -7,6 +7,8 @@
 // through registers): lane x of a wave-wide load writes LDS bytes [16 x, 16 x + 16) past a wave-uniform
 // base, so each lane simply fetches the global chunk that belongs at its LDS position.
 #pragma once
+#include <type_traits>
+
 #include "device_common.hpp"
 
 namespace chunk_attn {
@@ -137,6 +139,50 @@ __device__ __forceinline__ bf16x8 lds_chunk(const __bf16* tile, int row, int c) 
 // an accumulator tile presents its rows when it is reused as a B operand (device_common.hpp, "C-order").
 __host__ __device__ __forceinline__ int cperm(int p) {
   return (p & ~15) | ((p & 4) << 1) | ((p & 8) >> 1) | (p & 3);
+}
+
+// Chunk-major tile of 32 rows (rows of Q, dO, K or V: D / 8 chunks of 16 bytes each): chunk c of row r sits at slot
+// c * 32 + (r ^ 4 (c & 3)).  Such a tile serves both as rows (16-byte reads: operand X[row][k]) and transposed
+// (ds_read_b64_tr_b16: operand X^T[column][row]), both kinds of read bank-conflict free and their addresses one
+// per-lane base plus constants.  cm_elem: element offset of (row r, chunk c).
+__device__ __forceinline__ int cm_elem(int r, int c) { return (c * 32 + (r ^ ((c & 3) << 2))) * 8; }
+
+// LDS accesses as opaque instructions, for the software-pipelined kernels.  The compiler makes a wave wait for ALL of its
+// outstanding global->LDS copies before an LDS read it cannot tell apart from their destinations (the
+// transpose read in particular), which would serialise the copies of later stages with the reads of the
+// current one.  Issued like this, the reads are invisible to that logic; the kernels order them themselves with
+// explicit s_waitcnt lgkmcnt(n) (LDS operations of a wave complete in order).  `addr` is a byte address.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_asm_read16(unsigned addr) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ f32x4 lds_asm_read16f(unsigned addr) {
+  f32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_asm_read_tr(unsigned addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ void lds_asm_write16(unsigned addr, bf16x8 v) {
+  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ unsigned lds_addr(const lds_bf16* p) { return (unsigned)(uintptr_t)p; }
+__device__ __forceinline__ unsigned lds_addr(const lds_f32* p) { return (unsigned)(uintptr_t)p; }
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
 }
 
 }  // namespace chunk_attn
