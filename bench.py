@@ -72,7 +72,7 @@ def cpu_baseline():
 def recorded_traffic():
     """HBM-side bytes per launch of the dominant kernel, as measured by the two rocprofv3 counter runs that are
     summarised under profiles/ (this script cannot run the profiler on itself).  None if no summary is there."""
-    path = os.path.join(ROOT, "profiles", "bwd_dkv_kernel_bench_workload_hbm_traffic.md")
+    path = os.path.join(ROOT, "profiles", "bwd_dkv_pipe_kernel_bench_workload_hbm_traffic.md")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -227,7 +227,7 @@ def main():
                    "calls_per_step": 2 * n_launch, "flops_per_step": total_flops,
                    "seed_base": synth.BASE_SEED},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": "bwd_dkv_kernel<128>", "bound": "mfma", "achieved": round(achieved, 2),
+        "roofline": {"kernel": "bwd_dkv_pipe_kernel<128>", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": recorded_traffic(), "launches_per_step": n_launch,
                      "avg_launch_ms": round(bwd_k_ms / n_launch, 4),
