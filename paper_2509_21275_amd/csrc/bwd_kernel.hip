@@ -873,7 +873,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
       if (ROLE == 0) {
         // entry (query 8 (i / 4) + 4 hh + i % 4 of the tile, column of block kb) is visible iff 8 (i / 4) + i % 4 >= lim[kb]
         const bool valid = g < n_iter;
-        if (!valid || s_qt * BM < jrel_hi) {
+        if (__builtin_expect(!valid || s_qt * BM < jrel_hi, 0)) {  // rare: keep it out of the loop's straight line
           const int lim0 = valid ? jrel - s_qt * BM - 4 * hh : 0x40000000;
           const int lim1 = valid ? lim0 + 32 : 0x40000000;
 #pragma unroll
@@ -882,7 +882,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
             mask_c[1][i] = 8 * (i >> 2) + (i & 3) < lim1 ? -INFINITY : 0.f;
           }
           mask_set = true;
-        } else if (mask_set) {
+        } else if (__builtin_expect(mask_set, 0)) {
           mask_c[0] = zero16;
           mask_c[1] = zero16;
           mask_set = false;
