@@ -8,6 +8,15 @@
  * Heterogeneous Chunks").  Times come from the paper's cost model (section 3.2.1, Eq. 1 plus the
  * all-to-all term of Eq. 3, summed as in Eq. 4).  Everything here runs on the host; no GPU is touched.
  *
+ * Where the paper's sketch leaves a step open, this is what is implemented:
+ *   - "K workload-balanced slices" (line 1): the mesh whose largest slice time T_tot is as small as it can be, slices
+ *     being multiples of `align` except the last;
+ *   - the token threshold T_m (the paper refers to its repository): min(capacity, first mesh slice);
+ *   - time of a bucket with one more sequence (line 10): T_tot of the combined chunk, i.e. the per-chunk constants of
+ *     Eq. 1 and Eq. 3 are paid once; buckets are tried in ascending tot_time / tot_tokens, ties in order of creation;
+ *   - relaxing T_t (line 14): the smallest combined time among the buckets that have room for the sequence's tokens
+ *     (the minimum over all buckets would not terminate when the cheapest bucket is full).
+ *
  * All pointers are HOST pointers owned by the caller.  Functions return CHUNK_ATTN_OK (0) or a negative
  * code of chunk_attn.h (INVALID_ARG for null pointers, non-positive sizes or an output array that is
  * too small) and never throw or abort.
