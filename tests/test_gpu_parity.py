@@ -48,6 +48,10 @@ EDGE = [
     ("gqa2", [(0, 129, 0, 257)], 4, 2, 128),
     ("gqa8", [(0, 96, 0, 640), (96, 160, 640, 160)], 16, 2, 128),
     ("gqa3_odd_group", [(0, 65, 0, 193)], 6, 2, 64),
+    # walks of one, two and three pipeline stages (the pipelined kernels run their prologue / epilogue steps only)
+    ("d128_tiny_walks", [(0, 32, 0, 32), (32, 33, 32, 33), (65, 64, 65, 64), (129, 1, 129, 129), (130, 95, 258, 95)], 2, 2, 128),
+    # several segments with a context each, key ranges of 127 / 128 / 129 rows around a workgroup's 128 keys
+    ("d128_many_contexts", [(0, 40, 0, 127), (40, 40, 127, 128), (80, 40, 255, 129), (120, 200, 384, 513)], 8, 2, 128),
 ]
 
 
