@@ -9,12 +9,12 @@
  * all-to-all term of Eq. 3, summed as in Eq. 4).  Everything here runs on the host; no GPU is touched.
  *
  * Where the paper's sketch leaves a step open, this is what is implemented:
- *   - "K workload-balanced slices" (line 1): the mesh whose largest slice time T_tot is as small as it can be, slices
+ *   - "K workload-balanced slices" (the mesh step): the mesh whose largest slice time T_tot is as small as it can be, slices
  *     being multiples of `align` except the last;
  *   - the token threshold T_m (the paper refers to its repository): min(capacity, first mesh slice);
- *   - time of a bucket with one more sequence (line 10): T_tot of the combined chunk, i.e. the per-chunk constants of
+ *   - time of a bucket with one more sequence (the fit test of the packing loop): T_tot of the combined chunk, i.e. the per-chunk constants of
  *     Eq. 1 and Eq. 3 are paid once; buckets are tried in ascending tot_time / tot_tokens, ties in order of creation;
- *   - relaxing T_t (line 14): the smallest combined time among the buckets that have room for the sequence's tokens
+ *   - relaxing T_t (when no bucket accepts the sequence): the smallest combined time among the buckets that have room for the sequence's tokens
  *     (the minimum over all buckets would not terminate when the cheapest bucket is full).
  *
  * All pointers are HOST pointers owned by the caller.  Functions return CHUNK_ATTN_OK (0) or a negative
@@ -66,7 +66,7 @@ typedef struct {
 double chunk_plan_time(const chunk_cost_model* model, int64_t context, const int32_t* slice_lens, int32_t n);
 
 /*
- * Mesh (Algorithm 1, line 1): split a sequence of max_len tokens into K slices of (nearly) equal T_tot, slice
+ * Mesh (the first step of Algorithm 1): split a sequence of max_len tokens into K slices of (nearly) equal T_tot, slice
  * k having the slices before it as context.  Slice lengths are multiples of `align` (>= 1) except the last,
  * which takes the remainder; every slice has at least one token (K is lowered if max_len < K * align; the
  * number of slices actually produced is returned in *k_out).  Also returns the initial time threshold T_t

@@ -37,7 +37,7 @@ def balanced_mesh_time(m: Model, max_len: int, K: int, align: int) -> float:
     """The smallest possible value of the largest slice time when max_len tokens are cut into K consecutive slices, each
     a positive multiple of `align` except the last one (which takes what is left, at least one token), slice k having the
     slices before it as context: exhaustive dynamic programme over the cut positions.  ("K workload-balanced slices",
-    line 1 of Algorithm 1: the reading is that balanced means the largest T_tot is as small as it can be.)"""
+    the mesh step of Algorithm 1: the reading is that balanced means the largest T_tot is as small as it can be.)"""
     K = max(1, min(K, max_len // align))
     n_full = (max_len - 1) // align   # cut positions are align * 1 .. align * n_full (the last slice keeps >= 1 token)
     INF = float("inf")
@@ -72,34 +72,34 @@ class Bucket:
 
 
 def process(m: Model, capacity: int, lengths: List[int], mesh: List[int], time_threshold: float, token_threshold: int):
-    """Lines 2-16 of Algorithm 1 for a given mesh and thresholds (line 1 is checked separately, see
+    """Algorithm 1 after its mesh step, for a given mesh and thresholds (the mesh is checked separately, see
     balanced_mesh_time).  Returns (chunks, final time threshold); a chunk is (C, [(sequence, start, length), ...], I).
 
     Readings: a sequence longer than the first j mesh slices together yields j split chunks and a tail slice; the time
     of a bucket with one more sequence is T_tot of the combined chunk (the constants of Eq. 1 / Eq. 3 are paid once per
     chunk); buckets are tried in ascending order of tot_time / tot_tokens, ties in order of creation; when nothing fits,
-    the time threshold becomes the smallest combined time among the buckets that have room for the tokens (the listing
+    the time threshold becomes the smallest combined time among the buckets that have room for the tokens (the paper
     takes the minimum over all buckets, which need not terminate when the cheapest bucket is full).
     """
     split_chunks, tails, shorts = [], [], []
-    for i, n in enumerate(lengths):                      # line 2
+    for i, n in enumerate(lengths):                      # cut long sequences along the mesh
         pos, k = 0, 0
         while k < len(mesh) and pos + mesh[k] < n:
             split_chunks.append((pos, [(i, pos, mesh[k])], 1))
             pos += mesh[k]
             k += 1
         (tails if pos > 0 else shorts).append((i, pos, n - pos))
-    buckets = [Bucket(context=t[1], slices=[t]) for t in tails]                      # line 3
-    shorts.sort(key=lambda s: -t_tot(m, 0, [s[2]]))                                   # line 4 (stable)
+    buckets = [Bucket(context=t[1], slices=[t]) for t in tails]                      # one bucket per tail slice
+    shorts.sort(key=lambda s: -t_tot(m, 0, [s[2]]))                                   # by decreasing time (stable)
     T_t, T_m = time_threshold, token_threshold
-    for s in shorts:                                                                  # lines 5-15
-        if not buckets or min(b.tokens() for b in buckets) + s[2] > T_m:            # line 7
+    for s in shorts:                                                                  # packing loop
+        if not buckets or min(b.tokens() for b in buckets) + s[2] > T_m:            # no room anywhere
             buckets.append(Bucket(context=0, slices=[s]))
             continue
         while True:
             order = sorted(range(len(buckets)), key=lambda j: buckets[j].time(m) / buckets[j].tokens())
             placed = False
-            for j in order:                                                           # lines 9-12
+            for j in order:                                                           # first bucket that fits
                 b = buckets[j]
                 combined = t_tot(m, b.context, [x[2] for x in b.slices] + [s[2]])
                 if combined <= T_t and b.tokens() + s[2] <= T_m:
@@ -108,9 +108,9 @@ def process(m: Model, capacity: int, lengths: List[int], mesh: List[int], time_t
                     break
             if placed:
                 break
-            T_t = min(t_tot(m, b.context, [x[2] for x in b.slices] + [s[2]])          # line 14
+            T_t = min(t_tot(m, b.context, [x[2] for x in b.slices] + [s[2]])          # relax T_t
                       for b in buckets if b.tokens() + s[2] <= T_m)
-    chunks = split_chunks + [(b.context, b.slices, 0) for b in buckets]              # line 16
+    chunks = split_chunks + [(b.context, b.slices, 0) for b in buckets]              # buckets become chunks
     return chunks, T_t
 
 

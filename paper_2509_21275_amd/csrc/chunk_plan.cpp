@@ -110,7 +110,7 @@ int chunk_plan_build(const chunk_cost_model* model, int64_t capacity, const int3
     if (lengths[i] < 1) return CHUNK_ATTN_INVALID_ARG;
     max_len = std::max(max_len, lengths[i]);
   }
-  // line 1: mesh and thresholds
+  // mesh and thresholds
   std::vector<int32_t> mesh(K);
   int32_t k_eff = 0;
   double T_t = 0.0;
@@ -131,7 +131,7 @@ int chunk_plan_build(const chunk_cost_model* model, int64_t capacity, const int3
     return true;
   };
 
-  // line 2: a sequence longer than the first j mesh slices together gives j split chunks and a tail slice;
+  // splitting: a sequence longer than the first j mesh slices together gives j split chunks and a tail slice;
   // a sequence no longer than mesh[0] is "short"
   std::vector<Item> items;
   std::vector<int> tails, shorts;
@@ -150,7 +150,7 @@ int chunk_plan_build(const chunk_cost_model* model, int64_t capacity, const int3
     (pos > 0 ? tails : shorts).push_back((int)items.size() - 1);
   }
 
-  // lines 3-4: one bucket per tail slice (two tail slices never share a chunk); short sequences by decreasing time
+  // one bucket per tail slice (two tail slices never share a chunk); short sequences by decreasing time
   std::vector<Bucket> buckets;
   for (int t : tails) {
     Bucket b;
@@ -159,12 +159,12 @@ int chunk_plan_build(const chunk_cost_model* model, int64_t capacity, const int3
   }
   std::stable_sort(shorts.begin(), shorts.end(), [&](int a, int b) { return items[a].cost > items[b].cost; });
 
-  // lines 5-15: best-fit-decreasing over buckets ordered by time per token
+  // packing loop: best-fit-decreasing over buckets ordered by time per token
   for (int sidx : shorts) {
     const Item& s = items[sidx];
     int64_t min_tokens = -1;
     for (const Bucket& b : buckets) min_tokens = min_tokens < 0 ? b.tokens : std::min(min_tokens, b.tokens);
-    if (buckets.empty() || min_tokens + s.len > T_m) {  // line 7: no bucket has room for it
+    if (buckets.empty() || min_tokens + s.len > T_m) {  // no bucket has room for it
       Bucket b;
       b.shorts.push_back(sidx); b.cost = s.cost; b.tokens = s.len; b.order = (int)buckets.size();
       buckets.push_back(b);
@@ -177,7 +177,7 @@ int chunk_plan_build(const chunk_cost_model* model, int64_t capacity, const int3
                      [&](int a, int b) { return buckets[a].metric(cc) < buckets[b].metric(cc); });
     for (;;) {
       bool placed = false;
-      for (int bi : order) {  // lines 9-12
+      for (int bi : order) {  // first bucket, in that order, that stays within both thresholds
         Bucket& b = buckets[bi];
         if (b.cost + s.cost + chunk_const(m) <= T_t && b.tokens + s.len <= T_m) {
           b.shorts.push_back(sidx); b.cost += s.cost; b.tokens += s.len;
@@ -186,7 +186,7 @@ int chunk_plan_build(const chunk_cost_model* model, int64_t capacity, const int3
         }
       }
       if (placed) break;
-      // line 14: relax the time threshold to the cheapest bucket that has room for the tokens, then retry
+      // nothing fits: relax the time threshold to the cheapest bucket that has room for the tokens, then retry
       double best = -1.0;
       for (const Bucket& b : buckets)
         if (b.tokens + s.len <= T_m) {
@@ -197,7 +197,7 @@ int chunk_plan_build(const chunk_cost_model* model, int64_t capacity, const int3
     }
   }
 
-  // line 16: buckets -> hybrid chunks (tail slice first) and batched chunks
+  // buckets -> hybrid chunks (tail slice first) and batched chunks
   for (const Bucket& b : buckets) {
     const int first = ns;
     if (b.tail >= 0 && !push_slice(items[b.tail].seq, items[b.tail].start, items[b.tail].len)) return CHUNK_ATTN_INVALID_ARG;
