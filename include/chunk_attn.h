@@ -115,6 +115,19 @@ int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, co
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * chunk_attn_bwd with the key/value gradients kept in float32: dk, dv are DEVICE arrays of
+ * [total_kv, Hkv, head_dim] floats (16-byte aligned), everything else as in chunk_attn_bwd.  The rows of a
+ * key range receive the call's fp32 sums unrounded (accumulate_dkv == 0) or have them added in fp32
+ * (accumulate_dkv != 0), so the gradients of context rows that the slices of a split sequence build up over
+ * several calls (section 3.2.2) are rounded to bf16 once, by the caller, instead of once per slice.  The paper
+ * sizes these buffers at e bytes per element; this variant trades twice the memory for that accuracy.
+ * Same workspace as chunk_attn_bwd.
+ */
+int chunk_attn_bwd_f32kv(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                         const void* d_o, const float* lse, void* dq, float* dk, float* dv, int accumulate_dkv,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Number of unmasked (query, key) pairs per query head, sum_t (s C + s (s + 1) / 2): the
  * quantity behind the quadratic term of the paper's computation-time model (Eq. 1).
  * Forward costs 4 * head_dim flops per pair per query head, backward 10 * head_dim.

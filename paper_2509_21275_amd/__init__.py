@@ -46,6 +46,8 @@ def _load():
     lib.chunk_attn_fwd.restype = ctypes.c_int
     lib.chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
     lib.chunk_attn_bwd.restype = ctypes.c_int
+    lib.chunk_attn_bwd_f32kv.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
+    lib.chunk_attn_bwd_f32kv.restype = ctypes.c_int
     lib.chunk_attn_profile_events.argtypes = [vp, vp]
     lib.chunk_attn_profile_events.restype = ctypes.c_int
     return lib
@@ -144,6 +146,25 @@ def chunk_attn_bwd(desc, q, k, v, o, d_o, lse, dq, dk, dv, accumulate_dkv, works
     rc = _lib.chunk_attn_bwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
                              _ptr(dk), _ptr(dv), int(bool(accumulate_dkv)), _ptr(workspace),
                              workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != OK:
+        raise ChunkAttnError(rc)
+
+
+def chunk_attn_bwd_f32kv(desc, q, k, v, o, d_o, lse, dq, dk, dv, accumulate_dkv, workspace, stream=None) -> None:
+    """chunk_attn_bwd with float32 dk, dv (written, or added to in fp32)."""
+    import torch
+    qs = (desc.total_q, desc.num_q_heads, desc.head_dim)
+    ks = (desc.total_kv, desc.num_kv_heads, desc.head_dim)
+    for t, n in ((q, "q"), (o, "o"), (d_o, "d_o"), (dq, "dq")):
+        _check(t, torch.bfloat16, qs, n)
+    for t, n in ((k, "k"), (v, "v")):
+        _check(t, torch.bfloat16, ks, n)
+    for t, n in ((dk, "dk"), (dv, "dv")):
+        _check(t, torch.float32, ks, n)
+    _check(lse, torch.float32, (desc.num_q_heads, desc.total_q), "lse")
+    rc = _lib.chunk_attn_bwd_f32kv(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
+                                   _ptr(dk), _ptr(dv), int(bool(accumulate_dkv)), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != OK:
         raise ChunkAttnError(rc)
 

@@ -207,9 +207,10 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   return CHUNK_ATTN_OK;
 }
 
-int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
-                   const void* d_o, const float* lse, void* dq, void* dk, void* dv, int accumulate_dkv,
-                   void* workspace, size_t workspace_bytes, void* stream_v) {
+namespace {
+int bwd_any(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const void* d_o,
+            const float* lse, void* dq, void* dk, void* dv, bool dkv_f32, int accumulate_dkv, void* workspace,
+            size_t workspace_bytes, void* stream_v) {
   const int rc = validate(desc);
   if (rc != CHUNK_ATTN_OK) return rc;
   if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return CHUNK_ATTN_INVALID_ARG;
@@ -229,6 +230,7 @@ int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   a.dk = static_cast<__bf16*>(dk);
   a.dv = static_cast<__bf16*>(dv);
   a.accumulate = accumulate_dkv != 0;
+  a.dkv_f32 = dkv_f32;
   a.workspace = static_cast<char*>(workspace);
   const std::vector<char> blob = bwd_blob(P);
   hipError_t e = g_ring.upload(a.workspace, blob.data(), blob.size(), stream);
@@ -236,6 +238,20 @@ int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   e = launch_bwd(desc, a, P, stream);
   if (e != hipSuccess) return hip_fail(e, "backward launch");
   return CHUNK_ATTN_OK;
+}
+}  // namespace
+
+int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                   const void* d_o, const float* lse, void* dq, void* dk, void* dv, int accumulate_dkv,
+                   void* workspace, size_t workspace_bytes, void* stream_v) {
+  return bwd_any(desc, q, k, v, o, d_o, lse, dq, dk, dv, false, accumulate_dkv, workspace, workspace_bytes, stream_v);
+}
+
+int chunk_attn_bwd_f32kv(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                         const void* d_o, const float* lse, void* dq, float* dk, float* dv, int accumulate_dkv,
+                         void* workspace, size_t workspace_bytes, void* stream_v) {
+  if ((reinterpret_cast<uintptr_t>(dk) & 15) != 0 || (reinterpret_cast<uintptr_t>(dv) & 15) != 0) return CHUNK_ATTN_INVALID_ARG;
+  return bwd_any(desc, q, k, v, o, d_o, lse, dq, dk, dv, true, accumulate_dkv, workspace, workspace_bytes, stream_v);
 }
 
 }  // extern "C"

@@ -317,7 +317,29 @@ struct DkvParams {
   int32_t num_q_heads, num_kv_heads, group;
   float scale, scale_log2;
   int32_t accumulate;
+  int32_t out_f32;      // dk / dv point to fp32 arrays of the same shape
 };
+
+// Four consecutive elements of a dK / dV row: stored, or added to what is there, as bf16 or as fp32.
+__device__ __forceinline__ void dkv_store4(const DkvParams& p, __bf16* out, int64_t elem, float v0, float v1, float v2,
+                                           float v3) {
+  if (p.out_f32) {
+    f32x4* op = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + elem);
+    if (p.accumulate) {
+      const f32x4 old = *op;
+      v0 += old[0]; v1 += old[1]; v2 += old[2]; v3 += old[3];
+    }
+    const f32x4 nv = {v0, v1, v2, v3};
+    *op = nv;
+  } else {
+    bf16x4* op = reinterpret_cast<bf16x4*>(out + elem);
+    if (p.accumulate) {
+      const bf16x4 old = *op;
+      v0 += (float)old[0]; v1 += (float)old[1]; v2 += (float)old[2]; v3 += (float)old[3];
+    }
+    *op = pack4(v0, v1, v2, v3);
+  }
+}
 
 
 template <int D, int KB>  // KB: 32-key blocks per workgroup (2 KB waves)
@@ -596,14 +618,8 @@ __global__ __launch_bounds__(KB * 128, 4 / KB) void bwd_dkv_kernel(DkvParams p) 
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          float v0 = acc[db][4 * g] * f, v1 = acc[db][4 * g + 1] * f, v2 = acc[db][4 * g + 2] * f,
-                v3 = acc[db][4 * g + 3] * f;
-          bf16x4* op = reinterpret_cast<bf16x4*>(out + off + 32 * db + 8 * g + 4 * hh);
-          if (p.accumulate) {
-            const bf16x4 old = *op;
-            v0 += (float)old[0]; v1 += (float)old[1]; v2 += (float)old[2]; v3 += (float)old[3];
-          }
-          *op = pack4(v0, v1, v2, v3);
+          dkv_store4(p, out, off + 32 * db + 8 * g + 4 * hh, acc[db][4 * g] * f, acc[db][4 * g + 1] * f,
+                     acc[db][4 * g + 2] * f, acc[db][4 * g + 3] * f);
         }
     }
   }
@@ -1048,14 +1064,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            float v0 = acc[kb][db][4 * g] * fs, v1 = acc[kb][db][4 * g + 1] * fs, v2 = acc[kb][db][4 * g + 2] * fs,
-                  v3 = acc[kb][db][4 * g + 3] * fs;
-            bf16x4* op = reinterpret_cast<bf16x4*>(out + off + 32 * db + 8 * g + 4 * hh);
-            if (p.accumulate) {
-              const bf16x4 old = *op;
-              v0 += (float)old[0]; v1 += (float)old[1]; v2 += (float)old[2]; v3 += (float)old[3];
-            }
-            *op = pack4(v0, v1, v2, v3);
+            dkv_store4(p, out, off + 32 * db + 8 * g + 4 * hh, acc[kb][db][4 * g] * fs, acc[kb][db][4 * g + 1] * fs,
+                       acc[kb][db][4 * g + 2] * fs, acc[kb][db][4 * g + 3] * fs);
           }
       }
     }
@@ -1435,9 +1445,10 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
 
   if (!a.accumulate) {  // rows no segment covers receive no gradient
     for (const auto& gap : uncovered_kv_ranges(d)) {
-      const int64_t n16 = (int64_t)(gap.second - gap.first) * d->num_kv_heads * D / 8;
+      const int esz = a.dkv_f32 ? 4 : 2;  // bytes per element of dK / dV
+      const int64_t n16 = (int64_t)(gap.second - gap.first) * d->num_kv_heads * D * esz / 16;
       for (__bf16* base : {a.dk, a.dv}) {
-        u32x4* ptr = reinterpret_cast<u32x4*>(base + (int64_t)gap.first * d->num_kv_heads * D);
+        u32x4* ptr = reinterpret_cast<u32x4*>(reinterpret_cast<char*>(base) + (int64_t)gap.first * d->num_kv_heads * D * esz);
         hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, stream, ptr, n16);
       }
       if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1477,6 +1488,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
+    p.out_f32 = a.dkv_f32 ? 1 : 0;
     static_assert(DKV_KEYS == 128, "both kernels cover 128 keys per workgroup");
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;

@@ -58,6 +58,7 @@ struct BwdArgs {
   const float* lse;
   __bf16 *dq, *dk, *dv;
   bool accumulate;
+  bool dkv_f32;  // dk / dv are fp32 arrays
   char* workspace;
 };
 

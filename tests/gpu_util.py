@@ -16,7 +16,8 @@ def make_inputs(case, device="cuda"):
     return q, k, v, do
 
 
-def run_gpu(case, q, k, v, do=None, accumulate=False, dk_init=None, dv_init=None, scale=None, backward=True):
+def run_gpu(case, q, k, v, do=None, accumulate=False, dk_init=None, dv_init=None, scale=None, backward=True,
+            f32kv=False):
     import paper_2509_21275_amd as ca
     scale = case.scale if scale is None else scale
     desc = ca.make_desc(case.segs, case.num_q_heads, case.num_kv_heads, case.head_dim, case.total_q, case.total_kv,
@@ -32,8 +33,9 @@ def run_gpu(case, q, k, v, do=None, accumulate=False, dk_init=None, dv_init=None
     if accumulate:
         dk = dk_init.clone(); dv = dv_init.clone()
     else:
-        dk = torch.full_like(k, float("nan")); dv = torch.full_like(v, float("nan"))
-    ca.chunk_attn_bwd(desc, q, k, v, o, do, lse, dq, dk, dv, accumulate, ws)
+        kv_dtype = torch.float32 if f32kv else k.dtype
+        dk = torch.full_like(k, float("nan"), dtype=kv_dtype); dv = torch.full_like(v, float("nan"), dtype=kv_dtype)
+    (ca.chunk_attn_bwd_f32kv if f32kv else ca.chunk_attn_bwd)(desc, q, k, v, o, do, lse, dq, dk, dv, accumulate, ws)
     torch.cuda.synchronize()
     return o, lse, dq, dk, dv
 

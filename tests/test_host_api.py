@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol(ca):
         header = open(os.path.join(ROOT, "include", h)).read()
         header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
         names |= set(re.findall(r"\b((?:chunk_attn|chunk_plan|chunk_sched|fused_ce)_[a-z0-9_]+)\s*\(", header))
-    assert {"chunk_attn_fwd", "chunk_attn_bwd", "chunk_attn_workspace_bytes", "chunk_attn_validate",
+    assert {"chunk_attn_fwd", "chunk_attn_bwd", "chunk_attn_bwd_f32kv", "chunk_attn_workspace_bytes", "chunk_attn_validate",
             "chunk_attn_pair_count", "chunk_attn_strerror", "chunk_attn_profile_events",
             "chunk_plan_time", "chunk_plan_mesh", "chunk_plan_build", "chunk_plan_segments", "fused_ce_inplace",
             "chunk_sched_act_bytes", "chunk_sched_f2b", "chunk_sched_windows", "chunk_sched_solve_ckpt", "chunk_sched_group",
