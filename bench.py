@@ -99,7 +99,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus must be 1); the path shards by KV head or by "
-              "segment without communication, see DESIGN.md", file=sys.stderr)
+              "segment without communication", file=sys.stderr)
         sys.exit(2)
 
     import torch

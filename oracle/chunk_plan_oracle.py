@@ -3,7 +3,7 @@
 used by the product path.
 
 The steps are taken in the order of Algorithm 1.  Where the paper leaves a step open, the reading is the one
-stated in the function's docstring (and listed in the design doc).
+stated in the function's docstring.
 """
 from __future__ import annotations
 

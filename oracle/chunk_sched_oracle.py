@@ -6,7 +6,7 @@ the library and is never used by the product path.
 
 Stages are numbered p = 1 .. d_p as in the paper; chunks are numbered 0 .. n - 1 in forward order.
 
-Readings of points the paper leaves open (also listed in the design doc):
+Readings of points the paper leaves open:
   - N, the number of devices an activation is spread over, is d_p * d_s: only then do the activation footprint with
     l_ckpt checkpointed layers (section 3.2.3) and the coefficients of Algorithm 2 describe the same quantity;
   - forward order inside a 1F1B pipeline: sequences with more chunks first (ties: more tokens first, then input
