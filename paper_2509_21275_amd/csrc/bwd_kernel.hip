@@ -722,38 +722,41 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
       v_last[i] = (unsigned)(min(row, last_row) * (int)q_stride + off) * 2u;
     }
   }
-  int d_qt = it.qt_first, d_hg = 0, d_n = 0;  // (query tile, head in group, index) of the next stage to copy
-  int d_slot = 0;
-  int64_t d_roff = 0, d_rv = 0;  // wave-uniform element offsets of the stage's first row in Q / dO and in the row arrays
-  auto dma_locate = [&]() __attribute__((always_inline)) {
-    const int head = kvh * G + d_hg;
-    d_roff = (int64_t)(it.q_row_seg + d_qt * BM) * q_stride + (int64_t)head * D;
-    d_rv = ((int64_t)head * p.total_q_tiles + it.q_tile0) * 64 + d_qt * BM;
-  };
-  dma_locate();
-  const float* const rows_src = ((wave & 1) ? p.dsp : p.lse2p) + lane;
+  // Wave-uniform state of the copies, kept as running byte pointers so that a step spends only a handful of scalar
+  // instructions on it: the first row of the next stage to copy in Q and in dO, its LSE / D rows, the stages left in
+  // the current head's walk (counting that one), the heads left (counting the current one), the ring slot.
+  const int64_t roff0 = (int64_t)(it.q_row_seg + it.qt_first * BM) * q_stride + (int64_t)(kvh * G) * D;
+  const int64_t rv0 = ((int64_t)(kvh * G) * p.total_q_tiles + it.q_tile0) * 64 + it.qt_first * BM;
+  const char* d_q = reinterpret_cast<const char*>(p.q + roff0);
+  const char* d_g = reinterpret_cast<const char*>(p.d_o + roff0);
+  const char* d_r = reinterpret_cast<const char*>(((wave & 1) ? p.dsp : p.lse2p) + rv0);
+  const int64_t tile_bytes = (int64_t)BM * q_stride * 2;                 // to the next query tile of the same head
+  const int64_t head_bytes = (int64_t)D * 2 - (nqt - 1) * tile_bytes;    // to the first tile of the next head
+  const int64_t head_rows_bytes = (p.total_q_tiles * 64 - (int64_t)(nqt - 1) * BM) * 4;
+  int d_left = nqt, d_heads = G;
+  unsigned d_slot = 0;  // element offset of the ring slot inside the Q / dO rings (slot index x QT)
+  const unsigned lane4 = (unsigned)lane * 4u;
   lds_f32* const rows_dst = (wave & 1) ? dsum_s : lse_s;
-  auto dma_rows = [&]() __attribute__((always_inline)) { dma4(rows_src + d_rv, rows_dst + d_slot * RV); };
+  auto dma_rows = [&]() __attribute__((always_inline)) { dma4(d_r + lane4, rows_dst + d_slot / (QT / RV)); };
   auto dma_piece = [&](int i) __attribute__((always_inline)) {
     const int piece = i * NW + wave;  // wave-uniform; i < NP / NW: a piece of Q, else of dO
-    const unsigned voff = d_qt == it.n_qt - 1 ? v_last[i] : v_full[i];
-    const char* base = reinterpret_cast<const char*>((i < NP / NW ? p.q : p.d_o) + d_roff);
-    lds_bf16* dst = L + (i < NP / NW ? Q_OFF + piece * 512 : G_OFF + (piece - NP) * 512) + d_slot * QT;
+    const unsigned voff = d_left == 1 ? v_last[i] : v_full[i];  // the segment's last query tile
+    const char* base = i < NP / NW ? d_q : d_g;
+    lds_bf16* dst = L + (i < NP / NW ? Q_OFF + piece * 512 : G_OFF + (piece - NP) * 512) + d_slot;
     dma16(base + voff, dst);
   };
   auto dma_advance = [&]() __attribute__((always_inline)) {
-    if (d_n + 1 < n_iter) {
-      ++d_n;
-      if (++d_qt == it.n_qt) {
-        d_qt = it.qt_first;
-        ++d_hg;
-        dma_locate();
-      } else {
-        d_roff += BM * q_stride;
-        d_rv += BM;
-      }
+    if (__builtin_expect(d_left > 1, 1)) {
+      --d_left;
+      d_q += tile_bytes; d_g += tile_bytes; d_r += BM * 4;
+    } else {  // on to the next head of the group; after the last stage, stay on it
+      const bool more = d_heads > 1;
+      d_heads -= more ? 1 : 0;
+      d_left = more ? nqt : 1;
+      const int64_t hb = more ? head_bytes : 0, hr = more ? head_rows_bytes : 0;
+      d_q += hb; d_g += hb; d_r += hr;
     }
-    d_slot = d_slot == NS - 1 ? 0 : d_slot + 1;
+    d_slot = d_slot == (unsigned)((NS - 1) * QT) ? 0u : d_slot + (unsigned)QT;
   };
 
   // ---- per-lane operand addresses (elements) inside a tile, as in bwd_dkv_kernel ----
