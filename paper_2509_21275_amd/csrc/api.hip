@@ -23,43 +23,69 @@ int hip_fail(hipError_t e, const char* what) {
   return CHUNK_ATTN_HIP_ERROR;
 }
 
-// Pinned staging ring.  A slot is reused only after the copy that read it has completed.
+// Pinned staging buffers for the schedule uploads.  A buffer is reused only after the copy that read it has
+// completed; while the GPU is still busy with earlier calls the pool grows (up to kMaxBytes) instead of making the
+// caller wait, so that the host can plan and enqueue ahead of the GPU.
 struct StagingRing {
-  static constexpr int kSlots = 16;
+  static constexpr size_t kMaxBytes = (size_t)256 << 20;
   struct Slot {
     void* host = nullptr;
     size_t cap = 0;
     hipEvent_t ev = nullptr;
     bool in_flight = false;
-  } slots[kSlots];
-  int next = 0;
+  };
+  std::vector<Slot> slots;
+  size_t next = 0, total = 0;
   std::mutex mu;
 
   // Copies `bytes` from src into pinned memory and enqueues the upload to `dst` on `stream`.
   hipError_t upload(void* dst, const void* src, size_t bytes, hipStream_t stream) {
     std::lock_guard<std::mutex> lock(mu);
-    Slot& s = slots[next];
-    next = (next + 1) % kSlots;
     hipError_t e;
-    if (s.in_flight) {
-      if ((e = hipEventSynchronize(s.ev)) != hipSuccess) return e;
-      s.in_flight = false;
+    // the oldest buffers first: copies on one stream complete in order, so if those are pending the rest are too
+    Slot* s = nullptr;
+    for (size_t i = 0; i < std::min<size_t>(slots.size(), 4) && !s; ++i) {
+      Slot& c = slots[(next + i) % slots.size()];
+      if (c.in_flight) {
+        e = hipEventQuery(c.ev);
+        if (e == hipSuccess) c.in_flight = false;
+        else if (e != hipErrorNotReady) return e;
+      }
+      if (!c.in_flight) {
+        s = &c;
+        next = (next + i + 1) % slots.size();
+      }
     }
-    if (s.cap < bytes) {
-      if (s.host) {
-        if ((e = hipHostFree(s.host)) != hipSuccess) return e;
-        s.host = nullptr;
-        s.cap = 0;
+    if (!s) {
+      const size_t want = std::max<size_t>(align_up(bytes), 1 << 16);
+      if (slots.empty() || total + want <= kMaxBytes) {
+        slots.push_back(Slot{});
+        s = &slots.back();
+        next = 0;
+      } else {  // the pool is full and every copy is still pending: wait for the oldest
+        s = &slots[next];
+        next = (next + 1) % slots.size();
+        if ((e = hipEventSynchronize(s->ev)) != hipSuccess) return e;
+        s->in_flight = false;
+      }
+    }
+    if (s->cap < bytes) {
+      if (s->host) {
+        if ((e = hipHostFree(s->host)) != hipSuccess) return e;
+        total -= s->cap;
+        s->host = nullptr;
+        s->cap = 0;
       }
       const size_t cap = std::max<size_t>(align_up(bytes), 1 << 16);
-      if ((e = hipHostMalloc(&s.host, cap, hipHostMallocDefault)) != hipSuccess) return e;
-      s.cap = cap;
+      if ((e = hipHostMalloc(&s->host, cap, hipHostMallocDefault)) != hipSuccess) return e;
+      s->cap = cap;
+      total += cap;
     }
-    if (!s.ev && (e = hipEventCreateWithFlags(&s.ev, hipEventDisableTiming)) != hipSuccess) return e;
-    std::memcpy(s.host, src, bytes);
-    if ((e = hipMemcpyAsync(dst, s.host, bytes, hipMemcpyHostToDevice, stream)) != hipSuccess) return e;
-    if ((e = hipEventRecord(s.ev, stream)) != hipSuccess) return e;
-    s.in_flight = true;
+    if (!s->ev && (e = hipEventCreateWithFlags(&s->ev, hipEventDisableTiming)) != hipSuccess) return e;
+    std::memcpy(s->host, src, bytes);
+    if ((e = hipMemcpyAsync(dst, s->host, bytes, hipMemcpyHostToDevice, stream)) != hipSuccess) return e;
+    if ((e = hipEventRecord(s->ev, stream)) != hipSuccess) return e;
+    s->in_flight = true;
     return hipSuccess;
   }
 };
