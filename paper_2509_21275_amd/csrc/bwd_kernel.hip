@@ -31,6 +31,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 #ifndef DKV_PIPE_DIST
 #define DKV_PIPE_DIST 3
 #endif
+#ifndef DQ_PIPE_DIST
+#define DQ_PIPE_DIST 3  // stages the pipelined dQ kernel copies ahead
+#endif
 
 // ------------------------------------------------------------------------------------------------
 // bwd_pre: one workgroup per (64-row query tile, head); 4 threads per row.
@@ -1100,7 +1103,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
   constexpr int DK = D / 16;   // k-steps over the head dimension
   constexpr int DB = D / 32;   // 32-row blocks of dQ^T
   constexpr int KT = BN * D;   // elements per tile
-  constexpr int DIST = 3;      // stages copied ahead
+  constexpr int DIST = DQ_PIPE_DIST;  // stages copied ahead
   constexpr int NS = DIST + 3; // ring slots: stages t - 1 .. t + 1 in use, t + 2 .. t + 1 + DIST on their way
   constexpr int NF = 2 * DK + 2 * DB;  // operand fragments (mini-steps) per step: V rows, K rows, K^T
   constexpr int AHEAD = 4;             // fragments in flight
@@ -1471,7 +1474,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if constexpr (D == 128) {
-      const size_t smem = (size_t)2 * 6 * 32 * D * 2;  // 6 ring slots of a K and a V tile
+      const size_t smem = (size_t)2 * (DQ_PIPE_DIST + 3) * 32 * D * 2;  // ring slots of a K and a V tile
       if ((e = set_smem(&bwd_dq_pipe_kernel<D>, smem, &attr)) != hipSuccess) return e;
       hipLaunchKernelGGL((bwd_dq_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
     } else {

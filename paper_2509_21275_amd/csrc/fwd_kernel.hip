@@ -20,6 +20,10 @@
 #include <type_traits>
 
 #include "kernels.hpp"
+
+#ifndef FWD_PIPE_DIST
+#define FWD_PIPE_DIST 3  // stages the pipelined forward copies ahead of the one it computes on
+#endif
 #include "tiles.hpp"
 
 namespace chunk_attn {
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
   constexpr int DK = D / 16;   // k-steps of S^T = K Q^T
   constexpr int DB = D / 32;   // 32-row blocks of O^T
   constexpr int KT = BN * D;   // elements per tile
-  constexpr int DIST = 3;      // stages copied ahead
+  constexpr int DIST = FWD_PIPE_DIST;  // stages copied ahead
   constexpr int NS = DIST + 3; // ring slots: stages t - 1 .. t + 1 in use, t + 2 .. t + 1 + DIST on their way
   constexpr int NF = 2 * DB + DK;      // operand fragments (mini-steps) per step: V^T, then K rows
   constexpr int AHEAD = 4;             // fragments in flight
@@ -465,8 +469,6 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
   }
   bool risk = false;
   const float big = __builtin_amdgcn_exp2f(p.ref_limit);
-  bf16x2 ones;
-  ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
 
   // In program order mini-step m reads fragment m + 4: two instructions for the transposed fragments (0 .. 7 of this
   // step, 0 .. 3 of the next), one for the rows fragments (8 .. 15).  lgkm_wait(m) = number of LDS instructions between
@@ -497,7 +499,10 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
     auto finish_pair = [&](int jp) __attribute__((always_inline)) {
       bf16x2 w;
       w[0] = (__bf16)e_hold[0]; w[1] = (__bf16)e_hold[1];
-      ps[jp >> 3] = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps[jp >> 3], false);
+      // row sums with plain adds: a dot-product instruction next to MFMAs holds the wave up (it costs about as much
+      // as 14 cycles of the matrix pipe, an add 1 - 2)
+      ps[jp >> 3] += e_hold[0] + e_hold[1];
+      asm volatile("" : "+v"(ps[jp >> 3]));
       unsigned wu = __builtin_bit_cast(unsigned, w);
       asm volatile("" : "+v"(wu));
       pw[jp >> 3][jp & 7] = wu;
@@ -609,7 +614,7 @@ template <int D, int WAVES>
 static hipError_t launch_fwd_t(const FwdParams& p, int num_blocks, hipStream_t stream);
 
 static hipError_t launch_fwd_pipe(const FwdParams& p, int num_blocks, hipStream_t stream) {
-  const size_t smem = (size_t)2 * 6 * 32 * 128 * 2;  // 6 ring slots of a K and a V tile
+  const size_t smem = (size_t)2 * (FWD_PIPE_DIST + 3) * 32 * 128 * 2;  // ring slots of a K and a V tile
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_pipe_kernel<128>),
