@@ -31,6 +31,12 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_21275_amd.build` "
                           "(there is no fallback path)")
+    # PyTorch first: it brings its own HIP runtime, and a process must not end up with the system's runtime loaded
+    # by this library and PyTorch's tensors living in another one (both have the same soname; the first one loaded wins)
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     vp, sz = ctypes.c_void_p, ctypes.c_size_t
     dp = ctypes.POINTER(Desc)

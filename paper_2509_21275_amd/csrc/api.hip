@@ -25,9 +25,11 @@ int hip_fail(hipError_t e, const char* what) {
 
 // Pinned staging buffers for the schedule uploads.  A buffer is reused only after the copy that read it has
 // completed; while the GPU is still busy with earlier calls the pool grows (up to kMaxBytes) instead of making the
-// caller wait, so that the host can plan and enqueue ahead of the GPU.
+// caller wait, so that the host can plan and enqueue ahead of the GPU.  Buffers come in power-of-two sizes and are
+// never freed on the way (freeing pinned memory waits for the device): a buffer that is too small is simply skipped.
 struct StagingRing {
   static constexpr size_t kMaxBytes = (size_t)256 << 20;
+  static constexpr size_t kMinSlot = (size_t)256 << 10;
   struct Slot {
     void* host = nullptr;
     size_t cap = 0;
@@ -42,46 +44,57 @@ struct StagingRing {
   hipError_t upload(void* dst, const void* src, size_t bytes, hipStream_t stream) {
     std::lock_guard<std::mutex> lock(mu);
     hipError_t e;
-    // the oldest buffers first: copies on one stream complete in order, so if those are pending the rest are too
+    size_t want = kMinSlot;
+    while (want < bytes) want *= 2;
+    // a completed buffer that is large enough, oldest first (copies on one stream complete in order, so after a few
+    // pending ones the rest are pending too)
     Slot* s = nullptr;
-    for (size_t i = 0; i < std::min<size_t>(slots.size(), 4) && !s; ++i) {
-      Slot& c = slots[(next + i) % slots.size()];
+    int pending_seen = 0;
+    for (size_t i = 0; i < slots.size() && !s && pending_seen < 4; ++i) {
+      const size_t idx = (next + i) % slots.size();
+      Slot& c = slots[idx];
+      if (c.cap < bytes) continue;
       if (c.in_flight) {
         e = hipEventQuery(c.ev);
         if (e == hipSuccess) c.in_flight = false;
         else if (e != hipErrorNotReady) return e;
+        else ++pending_seen;
       }
       if (!c.in_flight) {
         s = &c;
-        next = (next + i + 1) % slots.size();
+        next = (idx + 1) % slots.size();
       }
     }
-    if (!s) {
-      const size_t want = std::max<size_t>(align_up(bytes), 1 << 16);
-      if (slots.empty() || total + want <= kMaxBytes) {
-        slots.push_back(Slot{});
-        s = &slots.back();
-        next = 0;
-      } else {  // the pool is full and every copy is still pending: wait for the oldest
-        s = &slots[next];
-        next = (next + 1) % slots.size();
-        if ((e = hipEventSynchronize(s->ev)) != hipSuccess) return e;
+    if (!s && total + want <= kMaxBytes) {  // grow
+      Slot n;
+      if ((e = hipHostMalloc(&n.host, want, hipHostMallocDefault)) != hipSuccess) return e;
+      n.cap = want;
+      if ((e = hipEventCreateWithFlags(&n.ev, hipEventDisableTiming)) != hipSuccess) return e;
+      total += want;
+      slots.push_back(n);
+      s = &slots.back();
+    }
+    if (!s) {  // the pool is at its limit: wait for the oldest buffer that is large enough
+      for (size_t i = 0; i < slots.size() && !s; ++i) {
+        Slot& c = slots[(next + i) % slots.size()];
+        if (c.cap >= bytes) s = &c;
+      }
+      if (s) {
+        if (s->in_flight && (e = hipEventSynchronize(s->ev)) != hipSuccess) return e;
         s->in_flight = false;
-      }
-    }
-    if (s->cap < bytes) {
-      if (s->host) {
+      } else {  // none is: replace the oldest one (this waits for the device)
+        s = &slots[next % slots.size()];
+        if (s->in_flight && (e = hipEventSynchronize(s->ev)) != hipSuccess) return e;
+        s->in_flight = false;
         if ((e = hipHostFree(s->host)) != hipSuccess) return e;
         total -= s->cap;
         s->host = nullptr;
         s->cap = 0;
+        if ((e = hipHostMalloc(&s->host, want, hipHostMallocDefault)) != hipSuccess) return e;
+        s->cap = want;
+        total += want;
       }
-      const size_t cap = std::max<size_t>(align_up(bytes), 1 << 16);
-      if ((e = hipHostMalloc(&s->host, cap, hipHostMallocDefault)) != hipSuccess) return e;
-      s->cap = cap;
-      total += cap;
     }
-    if (!s->ev && (e = hipEventCreateWithFlags(&s->ev, hipEventDisableTiming)) != hipSuccess) return e;
     std::memcpy(s->host, src, bytes);
     if ((e = hipMemcpyAsync(dst, s->host, bytes, hipMemcpyHostToDevice, stream)) != hipSuccess) return e;
     if ((e = hipEventRecord(s->ev, stream)) != hipSuccess) return e;
