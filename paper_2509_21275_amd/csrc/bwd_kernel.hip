@@ -1166,6 +1166,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
     lse2[u] = p.lse2p[slot];
     dsum[u] = p.dsp[slot];
   }
+  // -D of the unit's row in every element of a tile: the accumulation of dP^T starts from it, so that the vector work
+  // gets dP - D straight from the matrix pipe (a column of dP^T belongs to one query row)
+  f32x16 dneg[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dneg[u][i] = -dsum[u];
 
   // ---- staging: the 2 NP pieces of a stage (NP of K, then NP of V) are dealt to the waves round robin; a piece is
   // 64 consecutive slots of a chunk-major tile = two chunk columns of 32 rows.  Past the last stage the last one is
@@ -1311,8 +1318,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
       constexpr int j = decltype(j_c)::value;
       constexpr int u = j >> 3, dw = j & 7;
       bf16x2 w;
-      w[0] = (__bf16)(pf[u][2 * dw] * (dp[u][2 * dw] - dsum[u]));
-      w[1] = (__bf16)(pf[u][2 * dw + 1] * (dp[u][2 * dw + 1] - dsum[u]));
+      w[0] = (__bf16)(pf[u][2 * dw] * dp[u][2 * dw]);  // dp holds dP - D: its accumulation starts from -D
+      w[1] = (__bf16)(pf[u][2 * dw + 1] * dp[u][2 * dw + 1]);
       unsigned wu = __builtin_bit_cast(unsigned, w);
       asm volatile("" : "+v"(wu));
       pw[u][dw] = wu;
@@ -1338,7 +1345,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
         if constexpr (m < DK) {
           f32x16& d_ = dp[u];
           const bf16x8& b_ = gf[u][m];
-          if (m == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d_) : "v"(a_), "a"(b_));
+          const f32x16& n_ = dneg[u];
+          if (m == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d_) : "v"(a_), "a"(b_), "v"(n_));
           else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d_) : "v"(a_), "a"(b_));
         } else if constexpr (m < 2 * DK) {
           constexpr int ks = m - DK;
