@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(const __bf16* __restrict__
   acc += __shfl_xor(acc, 2);
   if (part == 0) {
     const int64_t slot = ((int64_t)head * total_q_tiles + job.image) * 64 + r;
-    dsp[slot] = valid ? acc : 0.f;
+    dsp[slot] = valid ? -acc : 0.f;  // stored negated: the kernels add it (or start an accumulation from it)
     lse2p[slot] = valid ? lse[(int64_t)head * total_q + job.src_row0 + r] * kLog2e : INFINITY;
   }
 }
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void bwd_dq_kernel(DqParams 
       }
       float ds[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) ds[i] = pe[i] * (dp[i] - dsum);
+      for (int i = 0; i < 16; ++i) ds[i] = pe[i] * (dp[i] + dsum);
       const bf16x8 f0 = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
       const bf16x8 f1 = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
       __builtin_amdgcn_sched_barrier(0);
@@ -583,8 +583,8 @@ __global__ __launch_bounds__(KB * 128, 4 / KB) void bwd_dkv_kernel(DkvParams p) 
         float w[16];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          w[i] = (float)p0[i] * (dp[i] - r4[i >> 2][i & 3]);
-          w[8 + i] = (float)p1[i] * (dp[8 + i] - r4[2 + (i >> 2)][i & 3]);
+          w[i] = (float)p0[i] * (dp[i] + r4[i >> 2][i & 3]);
+          w[8 + i] = (float)p1[i] * (dp[8 + i] + r4[2 + (i >> 2)][i & 3]);
         }
         const bf16x8 f0 = pack8(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]);
         const bf16x8 f1 = pack8(w[8], w[9], w[10], w[11], w[12], w[13], w[14], w[15]);
@@ -913,7 +913,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
       // hand-over (mini-step 0) and row values (mini-step 1) are issued between the MFMAs, so that the matrix pipe
       // restarts right after the barrier; the vector work starts at mini-step 4
       bf16x8 ph[2][2];
-      f32x4 r4[4];  // LSE (role A) or D (role B) of rows 8 g4 + 4 hh + 0..3
+      f32x4 r4[4];  // LSE (role A) or -D (role B) of rows 8 g4 + 4 hh + 0..3
       const unsigned pa = pex0 + (ROLE == 0 ? (g & 1) : ((g & 1) ^ 1)) * (PS * 2);
       const unsigned ra = rv0 + sR * (RV * 4);
       unsigned pw[2][8];
@@ -935,7 +935,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
           e_hold[q] = __builtin_amdgcn_exp2f(cur[kb][i] * c - r4[i >> 2][i & 3]);
           asm volatile("" : "+v"(e_hold[q]));
         } else {
-          const float e = (float)ph[kb][i >> 3][i & 7] * (cur[kb][i] - r4[i >> 2][i & 3]);
+          const float e = (float)ph[kb][i >> 3][i & 7] * (cur[kb][i] + r4[i >> 2][i & 3]);  // r4 = -D
           if constexpr (q == 0) {
             e_hold[0] = e;
             asm volatile("" : "+v"(e_hold[0]));
@@ -1172,7 +1172,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) dneg[u][i] = -dsum[u];
+    for (int i = 0; i < 16; ++i) dneg[u][i] = dsum[u];
 
   // ---- staging: the 2 NP pieces of a stage (NP of K, then NP of V) are dealt to the waves round robin; a piece is
   // 64 consecutive slots of a chunk-major tile = two chunk columns of 32 rows.  Past the last stage the last one is
