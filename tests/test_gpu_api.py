@@ -58,13 +58,19 @@ def test_accumulate_leaves_uncovered_rows_untouched_and_overwrite_zeroes_them(or
     assert rel_err(dv_acc.cpu()[cov], dV[c] - 2.0) <= TOL_GRAD
 
 
-def test_results_are_bit_reproducible_and_forward_is_recallable():
-    case = synth.scaled_case(4, 16)
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_results_are_bit_reproducible_and_forward_is_recallable(idx):
+    """Every kernel writes each output once, in a fixed order of accumulation (no atomics): repeated calls agree bit for
+    bit, for every chunk type and both head dimensions, whatever else the GPU was doing in between."""
+    case = synth.scaled_case(idx, 16, 5 if idx == 5 else None)
     q, k, v, do = make_inputs(case)
     a = run_gpu(case, q, k, v, do)
-    b = run_gpu(case, q, k, v, do)
-    for x, y in zip(a, b):
-        assert torch.equal(x, y)
+    other = synth.scaled_case(4 if idx != 4 else 3, 16)   # unrelated work between the two calls
+    run_gpu(other, *make_inputs(other))
+    for _ in range(3):
+        b = run_gpu(case, q, k, v, do)
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
 
 
 def test_workspace_too_small_and_null_pointers_are_reported():
