@@ -37,6 +37,7 @@
 #include <stdint.h>
 
 #include "chunk_attn.h"
+#include "chunk_plan.h"
 
 #ifdef __cplusplus
 extern "C" {
@@ -118,6 +119,31 @@ int chunk_sched_group(const chunk_sched_mem_model* model, const chunk_sched_chun
 int chunk_sched_simulate(int32_t d_p, int32_t n, int32_t n_split, const int32_t* f2b, const double* t_fwd,
                          const double* t_bwd, const double* t_recomp, const double* mem, double p2p, double* makespan,
                          double* busy, double* peak_mem, int32_t* peak_held);
+
+/*
+ * The whole solve for one batch (section 3.3 with the tuning of K of section 3.3 / 3.4.1, then section 3.4): for every
+ * slice number K in [k_min, k_max] (the paper tunes it in [1, d_p + 4]) the sequence processor of chunk_plan.h cuts
+ * the batch into chunks, the chunks are grouped into 1F1B pipelines and given their checkpointing; the K with the
+ * smallest estimated time wins (ties: the smaller K).  Estimated time of a plan:
+ *     sum over chunks of T_tot(chunk) * layers / d_p  +  sum over pipelines of (delta + F_hat * sum of the pipeline's C)
+ * with delta = (d_p - 1) * mean over the chunks of T_tot * layers / d_p and F_hat = fwd_fraction * mean T_tot (the
+ * forward share of one layer's time for an average chunk).  The cost model gives T_tot of one layer, forward +
+ * backward; `cost->n_devices` and `cost->dp` are used as given.
+ * A sequence, for the scheduler, is the split chunks of one long sequence in order followed by the chunk that holds
+ * its tail slice; every other chunk is a sequence of its own.
+ *
+ * Outputs: *best_k, *est_time; the chunks and slices of the winning plan (as chunk_plan_build; capacities max_chunks,
+ * max_slices: n_seqs * (k_max + 1) each always suffices); for every chunk its pipeline (pipelines numbered from 0)
+ * and its position in that pipeline's forward order; *n_pipelines; C of pipeline g at C[c_first[g] .. c_first[g + 1])
+ * (capacities: pipeline_of_chunk, fwd_pos_of_chunk max_chunks; c_first max_chunks + 1; C max_chunks * d_p).
+ * *feasible is 0 if no K in the range gives a plan that fits (then nothing else is written).
+ */
+int chunk_sched_plan_batch(const chunk_cost_model* cost, const chunk_sched_mem_model* mem, int64_t token_capacity,
+                           const int32_t* lengths, int32_t n_seqs, int32_t k_min, int32_t k_max, int32_t align,
+                           double fwd_fraction, double gap, int32_t* best_k, double* est_time, chunk_plan_chunk* chunks,
+                           int32_t max_chunks, int32_t* n_chunks, chunk_plan_slice* slices, int32_t max_slices,
+                           int32_t* n_slices, int32_t* pipeline_of_chunk, int32_t* fwd_pos_of_chunk,
+                           int32_t* n_pipelines, int32_t* C, int32_t* c_first, int32_t* feasible);
 
 #ifdef __cplusplus
 }

@@ -213,3 +213,43 @@ def simulate(d_p: int, n_split: int, f2b_: Sequence[int], t_fwd: Sequence[float]
         peak.append(pk_m)
         held.append(pk_n)
     return makespan, busy, peak, held
+
+
+def units_of_chunks(chunks):
+    """Sequences as the scheduler sees them, from the chunks (C, slices, I) of the sequence processor: the split
+    chunks of one long sequence in order followed by the chunk that holds its tail slice; every other chunk alone.
+    Returns lists of chunk indices."""
+    units = []
+    for c, (ctx, slices, is_split) in enumerate(chunks):
+        if is_split:
+            continue
+        head = []
+        if ctx > 0:
+            seq = slices[0][0]
+            head = sorted((j for j, (cj, sj, ij) in enumerate(chunks) if ij and sj[0][0] == seq), key=lambda j: chunks[j][0])
+        units.append(head + [c])
+    return units
+
+
+def plan_batch(plan_oracle, cost, mem: MemModel, lengths, ks, fwd_fraction: float, mesh_of):
+    """The whole solve (sections 3.3 and 3.4): for every K, chunks from the sequence processor's reference
+    (plan_oracle.process on the mesh and thresholds mesh_of(K) supplies), grouping and checkpointing by trying
+    everything; estimated time = sum of chunk times * layers / d_p + sum over pipelines of (delta + F_hat * sum C),
+    delta = (d_p - 1) * mean chunk time * layers / d_p, F_hat = fwd_fraction * mean chunk time.  Returns
+    (K, time, chunks, groups) of the best K (ties: the smaller K) or None."""
+    best = None
+    per_stage = mem.layers / mem.d_p
+    for K in ks:
+        mesh, t_t, t_m = mesh_of(K)
+        chunks, _ = plan_oracle.process(cost, 10 ** 12, lengths, mesh, t_t, t_m)
+        times = [plan_oracle.t_tot(cost, ctx, [s[2] for s in sl]) for ctx, sl, _ in chunks]
+        units = units_of_chunks(chunks)
+        mean_t = sum(times) / len(times)
+        sched_units = [[(sum(s[2] for s in chunks[c][1]), chunks[c][2]) for c in u] for u in units]
+        r = group(mem, sched_units, fwd_fraction * mean_t, (mem.d_p - 1) * mean_t * per_stage)
+        if r is None:
+            continue
+        total = sum(times) * per_stage + r[0]
+        if best is None or total < best[1] * (1.0 - 1e-12):
+            best = (K, total, chunks, [[units[u] for u in g] for g in r[1]])
+    return best

@@ -181,3 +181,49 @@ def chunk_sched_simulate(d_p: int, n_split: int, f2b: Sequence[int], t_fwd: Sequ
     _check(_lib.chunk_sched_simulate(d_p, n, n_split, _i32(f2b), _dbl(t_fwd), _dbl(t_bwd), flat(t_recomp), flat(mem), p2p,
                                      ctypes.byref(ms), busy, peak, held), "chunk_sched_simulate")
     return ms.value, list(busy)[:d_p], list(peak)[:d_p], list(held)[:d_p]
+
+
+@dataclass
+class BatchPlan:
+    k: int                          # the slice number K that won
+    est_time: float                 # estimated time of the batch (see include/chunk_sched.h)
+    chunks: list                    # chunk_plan.Chunk, as chunk_plan_build returns them
+    pipeline_of_chunk: List[int]
+    fwd_pos_of_chunk: List[int]     # position in its pipeline's forward order
+    C: List[List[int]]              # per pipeline: the n + d_p - 1 checkpointing variables
+
+
+def chunk_sched_plan_batch(cost, model: MemModel, token_capacity: int, lengths: Sequence[int], k_min: int, k_max: int,
+                           align: int, fwd_fraction: float = 1.0 / 3.0, gap: float = 0.0) -> Optional[BatchPlan]:
+    """The whole solve for one batch: K tuned in [k_min, k_max], sequence processor, grouping, checkpointing.
+    cost: chunk_plan.CostModel.  Returns None if no K gives a plan that fits."""
+    from . import chunk_plan as cp
+    _bind()
+    cp._bind()
+    if not getattr(_lib, "_plan_batch_bound", False):
+        i32, i32p, i64, dbl, dblp = ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.c_int64, ctypes.c_double, \
+            ctypes.POINTER(ctypes.c_double)
+        _lib.chunk_sched_plan_batch.argtypes = [ctypes.POINTER(cp.CostModel), ctypes.POINTER(_MemModel), i64, i32p, i32, i32, i32,
+                                                i32, dbl, dbl, i32p, dblp, ctypes.POINTER(cp._Chunk), i32, i32p,
+                                                ctypes.POINTER(cp._Slice), i32, i32p, i32p, i32p, i32p, i32p, i32p, i32p]
+        _lib.chunk_sched_plan_batch.restype = ctypes.c_int
+        _lib._plan_batch_bound = True
+    n = len(lengths)
+    cap = max(1, n * (k_max + 1))
+    chunks, slices = (cp._Chunk * cap)(), (cp._Slice * cap)()
+    pipe, pos, cf = _i32([0] * cap), _i32([0] * cap), _i32([0] * (cap + 1))
+    C = _i32([0] * (cap * model.d_p))
+    bk, nc, ns, npipe, ok, et = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), \
+        ctypes.c_double()
+    _check(_lib.chunk_sched_plan_batch(ctypes.byref(cost), ctypes.byref(model._c()), token_capacity, _i32(lengths), n, k_min,
+                                       k_max, align, fwd_fraction, gap, ctypes.byref(bk), ctypes.byref(et), chunks, cap,
+                                       ctypes.byref(nc), slices, cap, ctypes.byref(ns), pipe, pos, ctypes.byref(npipe), C, cf,
+                                       ctypes.byref(ok)), "chunk_sched_plan_batch")
+    if not ok.value:
+        return None
+    out = []
+    for c in chunks[:nc.value]:
+        sl = [(s.seq, s.start, s.len) for s in slices[c.first_slice:c.first_slice + c.num_slices]]
+        out.append(cp.Chunk(c.context, sl, bool(c.is_split), c.tokens, c.time))
+    return BatchPlan(bk.value, et.value, out, list(pipe[:nc.value]), list(pos[:nc.value]),
+                     [list(C[cf[g]:cf[g + 1]]) for g in range(npipe.value)])

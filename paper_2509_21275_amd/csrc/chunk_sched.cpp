@@ -689,4 +689,116 @@ int chunk_sched_simulate(int32_t d_p, int32_t n, int32_t n_split, const int32_t*
   return CHUNK_ATTN_OK;
 }
 
+int chunk_sched_plan_batch(const chunk_cost_model* cost, const chunk_sched_mem_model* mem, int64_t token_capacity,
+                           const int32_t* lengths, int32_t n_seqs, int32_t k_min, int32_t k_max, int32_t align,
+                           double fwd_fraction, double gap, int32_t* best_k, double* est_time, chunk_plan_chunk* chunks,
+                           int32_t max_chunks, int32_t* n_chunks, chunk_plan_slice* slices, int32_t max_slices,
+                           int32_t* n_slices, int32_t* pipeline_of_chunk, int32_t* fwd_pos_of_chunk,
+                           int32_t* n_pipelines, int32_t* C, int32_t* c_first, int32_t* feasible) {
+  if (!cost || !model_ok(mem) || !lengths || !best_k || !est_time || !chunks || !n_chunks || !slices || !n_slices ||
+      !pipeline_of_chunk || !fwd_pos_of_chunk || !n_pipelines || !C || !c_first || !feasible || n_seqs < 1 || k_min < 1 ||
+      k_max < k_min || align < 1 || token_capacity < 1 || !(fwd_fraction > 0.0) || !(fwd_fraction < 1.0) || !(gap >= 0.0))
+    return CHUNK_ATTN_INVALID_ARG;
+  const int d_p = mem->d_p;
+  const double per_stage = (double)mem->layers / d_p;
+  struct Best {
+    bool ok = false;
+    int k = 0;
+    double time = 0.0;
+    std::vector<chunk_plan_chunk> chunks;
+    std::vector<chunk_plan_slice> slices;
+    std::vector<int32_t> pipe, pos, C, c_first;
+    int n_pipes = 0;
+  } best;
+  for (int K = k_min; K <= k_max; ++K) {
+    const int cap = n_seqs * (K + 1);
+    std::vector<chunk_plan_chunk> ch(cap);
+    std::vector<chunk_plan_slice> sl(cap);
+    int32_t nc = 0, ns = 0;
+    int rc = chunk_plan_build(cost, token_capacity, lengths, n_seqs, K, align, ch.data(), cap, &nc, sl.data(), cap, &ns,
+                              nullptr, nullptr);
+    if (rc != CHUNK_ATTN_OK) return rc;
+    ch.resize(nc);
+    sl.resize(ns);
+    // sequences as the scheduler sees them
+    std::vector<std::vector<int>> units;
+    {
+      std::vector<std::vector<int>> split_of(n_seqs);
+      for (int c = 0; c < nc; ++c)
+        if (ch[c].is_split) split_of[sl[ch[c].first_slice].seq].push_back(c);
+      for (auto& v : split_of)
+        std::sort(v.begin(), v.end(), [&](int a, int b) { return ch[a].context < ch[b].context; });
+      for (int c = 0; c < nc; ++c) {
+        if (ch[c].is_split) continue;
+        std::vector<int> u;
+        if (ch[c].context > 0) {
+          std::vector<int>& head = split_of[sl[ch[c].first_slice].seq];
+          u = head;
+          head.clear();
+        }
+        u.push_back(c);
+        units.push_back(u);
+      }
+      for (const auto& v : split_of)
+        if (!v.empty()) return CHUNK_ATTN_INVALID_ARG;  // a split chunk without its tail: cannot happen
+    }
+    std::vector<chunk_sched_chunk> sc;
+    std::vector<int32_t> first{0}, chunk_of;  // chunk_of[i]: planner chunk behind scheduler chunk i
+    double sum_t = 0.0;
+    for (const auto& u : units) {
+      for (int c : u) {
+        sc.push_back(chunk_sched_chunk{ch[c].tokens, ch[c].is_split});
+        chunk_of.push_back(c);
+        sum_t += ch[c].time;
+      }
+      first.push_back((int32_t)sc.size());
+    }
+    const int n_units = (int)units.size();
+    const double mean_t = sum_t / nc;
+    const double delta = (d_p - 1) * mean_t * per_stage, f_hat = fwd_fraction * mean_t;
+    std::vector<int32_t> gou(n_units), order(nc), of(n_units + 1), cf(n_units + 1), Cv((size_t)nc + (size_t)n_units * (d_p - 1) + 1);
+    int32_t ng = 0, ok = 0;
+    double cost_g = 0.0;
+    rc = chunk_sched_group(mem, sc.data(), first.data(), n_units, f_hat, delta, gap, gou.data(), &ng, &cost_g, order.data(),
+                           of.data(), Cv.data(), cf.data(), &ok);
+    if (rc != CHUNK_ATTN_OK) return rc;
+    if (!ok) continue;
+    const double total = sum_t * per_stage + cost_g;
+    if (best.ok && !(total < best.time * (1.0 - 1e-12))) continue;
+    best.ok = true;
+    best.k = K;
+    best.time = total;
+    best.chunks = ch;
+    best.slices = sl;
+    best.n_pipes = ng;
+    best.pipe.assign(nc, -1);
+    best.pos.assign(nc, -1);
+    for (int g = 0; g < ng; ++g)
+      for (int i = of[g]; i < of[g + 1]; ++i) {
+        best.pipe[chunk_of[order[i]]] = g;
+        best.pos[chunk_of[order[i]]] = i - of[g];
+      }
+    best.C.assign(Cv.begin(), Cv.begin() + cf[ng]);
+    best.c_first.assign(cf.begin(), cf.begin() + ng + 1);
+  }
+  if (!best.ok) {
+    *feasible = 0;
+    return CHUNK_ATTN_OK;
+  }
+  if ((int)best.chunks.size() > max_chunks || (int)best.slices.size() > max_slices) return CHUNK_ATTN_INVALID_ARG;
+  std::copy(best.chunks.begin(), best.chunks.end(), chunks);
+  std::copy(best.slices.begin(), best.slices.end(), slices);
+  std::copy(best.pipe.begin(), best.pipe.end(), pipeline_of_chunk);
+  std::copy(best.pos.begin(), best.pos.end(), fwd_pos_of_chunk);
+  std::copy(best.C.begin(), best.C.end(), C);
+  std::copy(best.c_first.begin(), best.c_first.end(), c_first);
+  *n_chunks = (int32_t)best.chunks.size();
+  *n_slices = (int32_t)best.slices.size();
+  *n_pipelines = best.n_pipes;
+  *best_k = best.k;
+  *est_time = best.time;
+  *feasible = 1;
+  return CHUNK_ATTN_OK;
+}
+
 }  // extern "C"

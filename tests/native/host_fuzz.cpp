@@ -112,6 +112,26 @@ int main(int argc, char** argv) {
       REQUIRE(makespan > 0);
     }
     for (int k = 0; k < n_ch; ++k) REQUIRE(seen[k]);
+    // ---- the whole solve on the same batch ----
+    {
+      const int k_max = 1 + uni(0, 3), capb = n_seqs * (k_max + 1);
+      std::vector<chunk_plan_chunk> bc(capb);
+      std::vector<chunk_plan_slice> bs(capb);
+      std::vector<int32_t> pipe(capb), pos(capb), cfb(capb + 1), Cb((size_t)capb * d_p);
+      int32_t bk = 0, bnc = 0, bns = 0, bnp = 0, bok = 0;
+      double bt = 0;
+      REQUIRE(chunk_sched_plan_batch(&cm, &mm, 1 << 20, lengths.data(), n_seqs, 1, k_max, align, 1.0 / 3.0, 0.05, &bk, &bt, bc.data(), capb,
+                                     &bnc, bs.data(), capb, &bns, pipe.data(), pos.data(), &bnp, Cb.data(), cfb.data(), &bok) == CHUNK_ATTN_OK);
+      if (bok) {
+        REQUIRE(bk >= 1 && bk <= k_max && bt > 0 && bnc >= 1 && bnp >= 1);
+        std::vector<int> per_pipe(bnp, 0);
+        for (int c = 0; c < bnc; ++c) {
+          REQUIRE(pipe[c] >= 0 && pipe[c] < bnp && pos[c] >= 0);
+          ++per_pipe[pipe[c]];
+        }
+        for (int g = 0; g < bnp; ++g) REQUIRE(cfb[g + 1] - cfb[g] == per_pipe[g] + d_p - 1);
+      }
+    }
   }
   std::printf("ok %u cases (%d did not fit, %d needed checkpointing)\n", n_cases, n_infeasible, n_ckpt);
   return 0;

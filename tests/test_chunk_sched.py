@@ -222,3 +222,43 @@ def test_invalid_arguments():
                       m_ms=[0.0, 0.0])
     with pytest.raises(ChunkAttnError):
         cs.chunk_sched_solve_ckpt(bad, [(10, 0)], [0], 1)
+
+
+def test_plan_batch_matches_the_composed_reference():
+    """The whole solve (K tuning, sequence processor, grouping, checkpointing) on batches small enough for the
+    reference to try everything: same K, same estimated time, same chunks; every chunk in one pipeline."""
+    import chunk_plan_oracle as po
+    from paper_2509_21275_amd import chunk_plan as cp
+    rng = random.Random(131)
+    done = 0
+    for _ in range(30):
+        d_p = rng.randint(1, 2)
+        m, om = models(d_p=d_p, d_s=1, layers=2 * d_p)
+        pm = po.Model(alpha1=1.0, alpha2=64.0, beta1=float(rng.choice([0, 4096])))
+        cm = cp.CostModel(pm.alpha1, pm.alpha2, pm.beta1, 0.0, 0.0, 1, 1)
+        lengths = [rng.choice([256, 384, 512, 1024, 2048]) for _ in range(rng.randint(1, 3))]
+        align, ks = 128, [1, 2]
+
+        def mesh_of(K):
+            return cp.chunk_plan_mesh(cm, max(lengths), K, align, 1 << 20)
+
+        # keep only batches the reference can enumerate (at most 4 chunks per K)
+        sizes = [len(po.process(pm, 10 ** 12, lengths, *mesh_of(K))[0]) for K in ks]
+        if max(sizes) + d_p - 1 > 5:
+            continue
+        biggest = max(o.act_bytes(om, d_p, n, 1, 0) for n in lengths)
+        m.capacity = om.capacity = rng.uniform(0.6, 2.5) * biggest
+        want = o.plan_batch(po, pm, om, lengths, ks, 1.0 / 3.0, mesh_of)
+        got = cs.chunk_sched_plan_batch(cm, m, 1 << 20, lengths, ks[0], ks[-1], align, 1.0 / 3.0, 0.0)
+        if want is None:
+            assert got is None
+            continue
+        assert got is not None and got.k == want[0]
+        assert got.est_time == pytest.approx(want[1], rel=1e-9)
+        assert [(c.context, c.slices, int(c.is_split)) for c in got.chunks] == [(ctx, sl, i) for ctx, sl, i in want[2]]
+        assert all(0 <= p < len(got.C) for p in got.pipeline_of_chunk)
+        for g in range(len(got.C)):  # positions inside a pipeline are a permutation, C has n + d_p - 1 entries
+            pos = sorted(got.fwd_pos_of_chunk[c] for c in range(len(got.chunks)) if got.pipeline_of_chunk[c] == g)
+            assert pos == list(range(len(pos))) and len(got.C[g]) == len(pos) + d_p - 1
+        done += 1
+    assert done >= 8

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol(ca):
             "chunk_attn_pair_count", "chunk_attn_strerror", "chunk_attn_profile_events",
             "chunk_plan_time", "chunk_plan_mesh", "chunk_plan_build", "chunk_plan_segments", "fused_ce_inplace",
             "chunk_sched_act_bytes", "chunk_sched_f2b", "chunk_sched_windows", "chunk_sched_solve_ckpt", "chunk_sched_group",
-            "chunk_sched_simulate"} <= names
+            "chunk_sched_simulate", "chunk_sched_plan_batch"} <= names
     lib = ctypes.CDLL(ca.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
