@@ -109,6 +109,41 @@ def test_oracle_structure(seed):
     check_structure(chunks, lengths, mesh, T_t, T_m, m)
 
 
+# The packing loop of Algorithm 1 (section 3.3) on a batch small enough to follow with pencil and paper.  Cost model
+# T = (C + s0)^2 - C^2 + sum of s^2 over the other slices (alpha1 = 1, nothing else), mesh {8, 4}, T_t = 45, T_m = 7.
+#   lengths 14, 11, 9 are cut by the mesh: split chunks (0, 8), (8, 4) | (0, 8) | (0, 8) and the tail slices
+#     A = (C 12, 2 tokens): 14^2 - 12^2 = 52, ratio 26;  B = (C 8, 3 tokens): 11^2 - 8^2 = 57, ratio 19;
+#     C = (C 8, 1 token): 9^2 - 8^2 = 17, ratio 17;      one bucket each.
+#   short sequences by decreasing time: 7 (49), 5 (25), 4 (16), 3 (9), 1 (1).
+#   7: the emptiest bucket has 1 token, 1 + 7 > T_m: a new bucket D = [7] (time 49, ratio 7).
+#   5: buckets by ascending ratio D 7, C 17, B 19, A 26.  D: 49 + 25 > 45.  C: 17 + 25 = 42 <= 45, 6 tokens: placed.
+#      C is now [1, 5]: time 42, 6 tokens, ratio 7.
+#   4: C (7; created before D): 10 tokens > 7.  D: 11 tokens.  B: 57 + 16 = 73 > 45.  A: 52 + 16 = 68 > 45.  Nothing
+#      fits: T_t becomes the cheapest combined time among the buckets with room for 4 tokens, min(73, 68) = 68 (the
+#      cheapest of all, C with 58, is full: taking it would never end).  Again: C, D full, B 73 > 68, A 68 <= 68:
+#      placed.  A is now [2, 4]: time 68, 6 tokens, ratio 11.33.
+#   3: C, D full.  A (11.33): 68 + 9 > 68.  B (19): 57 + 9 = 66 <= 68, 6 tokens: placed.  B: ratio 11.
+#   1: C (7): 42 + 1 = 43 <= 68, 7 tokens: placed.  (Descending ratio order would take B: A 69 > 68, B 67 fits;
+#      so would a best fit by time, B leaving 1 and C 25.)
+def test_packing_loop_worked_example():
+    m = orc.Model(alpha1=1.0, alpha2=0.0, beta1=0.0)
+    lengths = [14, 11, 9, 7, 5, 4, 3, 1]
+    # given in an order that is not the sorted one: the loop has to sort the short sequences itself
+    perm = [4, 0, 7, 2, 6, 1, 3, 5]
+    chunks, T_t = orc.process(m, 10 ** 9, [lengths[i] for i in perm], [8, 4], 45.0, 7)
+    seq = {length: i for i, length in enumerate(lengths[j] for j in perm)}   # lengths are distinct: name sequences by length
+    want = [
+        (0, [(seq[14], 0, 8)], 1), (8, [(seq[14], 8, 4)], 1), (0, [(seq[11], 0, 8)], 1), (0, [(seq[9], 0, 8)], 1),
+        (12, [(seq[14], 12, 2), (seq[4], 0, 4)], 0),
+        (8, [(seq[11], 8, 3), (seq[3], 0, 3)], 0),
+        (8, [(seq[9], 8, 1), (seq[5], 0, 5), (seq[1], 0, 1)], 0),
+        (0, [(seq[7], 0, 7)], 0),
+    ]
+    assert T_t == 68.0
+    key = lambda c: (c[1][0][0], c[1][0][1])       # chunks compared as a set: by (sequence, start) of the first slice
+    assert sorted(chunks, key=key) == sorted(want, key=key)
+
+
 # ------------------------------------------------------------------ C++ planner against the oracle
 ca_plan = pytest.importorskip("paper_2509_21275_amd.chunk_plan")
 
@@ -163,6 +198,27 @@ def test_build_matches_oracle(seed):
             assert c.time == orc.t_tot(m, c.context, [s[2] for s in c.slices])
             assert c.tokens == sum(s[2] for s in c.slices)
         check_structure(want, lengths, mesh, want_T, T_m, m)
+
+
+def test_build_worked_example():
+    # the planner of the library on the batch of test_packing_loop_worked_example, thresholds from its own mesh step:
+    # alpha1 = 1 and a longest sequence of 14 cut into slices of 10 and 4 (10^2 = 100 >= 14^2 - 10^2 = 96; 9 and 5
+    # give 115) make T_t = 100, T_m = 10.  Sequences 14 and 11 lose a 10-token slice: tails (C 10, 4 tokens; 96,
+    # ratio 24) and (C 10, 1 token; 21, ratio 21).  Shorts 9, 7, 5, 4, 3, 1: 9 -> the 1-token bucket (21 + 81 > 100 but
+    # the 4-token bucket has 13 tokens; nothing fits, T_t = 102 (the only bucket with room), placed there, 10 tokens,
+    # full).  7: 4 + 7 > 10: new bucket [7] (49, ratio 7).  5 (ratios 7, 10.2, 24): [7] has no room, the full one
+    # neither, A: 96 + 25 = 121 > 102, 9 tokens: T_t = 121, placed (ratio 13.4).  4: [7] 11 tokens, full, A 13 tokens:
+    # the emptiest bucket has 7 tokens, 7 + 4 > 10: new bucket [4] (16, ratio 4).  3: [4] first: 25 <= 121, 7 tokens.
+    # 1: [4, 3] (25 / 7 = 3.6): 26, 8 tokens: placed.
+    m = orc.Model(alpha1=1.0, alpha2=0.0, beta1=0.0)
+    lengths = [14, 11, 9, 7, 5, 4, 3, 1]
+    got, got_T, got_Tm = ca_plan.chunk_plan_build(to_c(m), 10 ** 9, lengths, 2, 1)
+    assert (got_T, got_Tm) == (121.0, 10)
+    want = [(0, [(0, 0, 10)], 1), (0, [(1, 0, 10)], 1),
+            (10, [(0, 10, 4), (4, 0, 5)], 0), (10, [(1, 10, 1), (2, 0, 9)], 0),
+            (0, [(3, 0, 7)], 0), (0, [(5, 0, 4), (6, 0, 3), (7, 0, 1)], 0)]
+    key = lambda c: (c[1][0][0], c[1][0][1])
+    assert sorted(((c.context, c.slices, int(c.is_split)) for c in got), key=key) == sorted(want, key=key)
 
 
 def test_segments_match():

@@ -262,3 +262,19 @@ def test_plan_batch_matches_the_composed_reference():
             assert pos == list(range(len(pos))) and len(got.C[g]) == len(pos) + d_p - 1
         done += 1
     assert done >= 8
+
+
+def test_plan_batch_worked_example():
+    """The batch of tests/test_chunk_sched_oracle.py::test_plan_batch_worked_example, whose answer is derived by hand
+    there (K = 2, estimated time 128, one pipeline), through the library."""
+    from paper_2509_21275_amd import chunk_plan as cp
+    m, _ = models(d_p=2, d_s=1, layers=2)
+    cm = cp.CostModel(1.0, 0.0, 0.0, 0.0, 0.0, 1, 1)
+    got = cs.chunk_sched_plan_batch(cm, m, 1 << 20, [8, 4, 4], 1, 2, 1, 1.0 / 3.0, 0.0)
+    assert got is not None and got.k == 2 and got.est_time == 128.0
+    assert [(c.context, c.slices, int(c.is_split)) for c in got.chunks] == \
+        [(0, [(0, 0, 6)], 1), (6, [(0, 6, 2), (1, 0, 4)], 0), (0, [(2, 0, 4)], 0)]
+    assert got.pipeline_of_chunk == [0, 0, 0] and got.fwd_pos_of_chunk == [0, 1, 2]
+    assert got.C == [[0, 0, 0, 0]]
+    only1 = cs.chunk_sched_plan_batch(cm, m, 1 << 20, [8, 4, 4], 1, 1, 1, 1.0 / 3.0, 0.0)
+    assert only1.k == 1 and only1.est_time == 144.0

@@ -257,3 +257,42 @@ def test_grouping_is_none_when_a_sequence_can_never_fit():
     m = model(d_p=1, d_s=1, layers=2)
     m.capacity = 0.5 * o.act_bytes(m, 1, 4096, 0, 2)
     assert o.group(m, [[(4096, 0)], [(16, 0)]], 1.0, 1.0) is None
+
+
+# ---- the whole solve of a batch (sections 3.3 and 3.4.2) and the sequences the scheduler sees ----
+
+def test_units_of_chunks_on_the_mesh_example():
+    # Section 3.3's example, mesh {8K, 4K, 2K}: a 13K sequence is an 8K and a 4K split chunk plus a 1K tail slice, a 9K
+    # one an 8K split chunk plus a 1K tail, a 14K one 8K + 4K + a 2K tail; a 3K sequence is not cut.  The scheduler
+    # sees one sequence per tail-holding chunk, its split chunks first, in order of their context.
+    K = 1024
+    chunks = [(0, [(0, 0, 8 * K)], 1), (8 * K, [(3, 8 * K, 4 * K)], 1), (0, [(1, 0, 8 * K)], 1), (0, [(3, 0, 8 * K)], 1),
+              (8 * K, [(0, 8 * K, 4 * K)], 1),
+              (12 * K, [(0, 12 * K, K)], 0), (8 * K, [(1, 8 * K, K), (2, 0, 3 * K)], 0), (12 * K, [(3, 12 * K, 2 * K)], 0)]
+    assert o.units_of_chunks(chunks) == [[0, 4, 5], [2, 6], [3, 1, 7]]
+    assert o.units_of_chunks([(0, [(0, 0, 5)], 0), (0, [(1, 0, 7), (2, 0, 1)], 0)]) == [[0], [1]]
+
+
+def test_plan_batch_worked_example():
+    # Lengths 8, 4, 4; cost T = (C + s0)^2 - C^2 + sum of the other s^2; two stages, two layers (one per stage), memory
+    # to spare, so nothing is checkpointed and a pipeline costs delta = (d_p - 1) * mean chunk time.
+    #   K = 1: mesh {8}, T_t = 64, T_m = 8.  Nothing is cut.  8 opens a bucket (64); 4: 8 + 4 > T_m, a second bucket
+    #     (16); 4: 4 + 4 <= 8, ratios 64 / 8 = 8 and 16 / 4 = 4: the second bucket first, 16 + 16 <= 64: placed.
+    #     Chunks [8], [4, 4]: times 64, 32, sum 96, mean 48; every sequence has one chunk: one pipeline.  96 + 48 = 144.
+    #   K = 2: 8 = 6 + 2 (36 and 64 - 36 = 28; 5 + 3 gives 39), T_t = 36, T_m = 6.  The 8 leaves a split chunk (0, 6)
+    #     and a tail (C 6, 2 tokens, 28).  4: 2 + 4 <= 6 but 28 + 16 = 44 > 36: T_t becomes 44, placed.  4: 6 + 4 > 6: a
+    #     new bucket.  Chunks: split [6] 36, hybrid (C 6) [2, 4] 44, batched [4] 16: sum 96, mean 32.  Sequences: one
+    #     of two chunks, one of one chunk.  One pipeline for both: 96 + 32 = 128; one each: 96 + 64 = 160.
+    #   K = 2 wins with 128, one pipeline, the longer sequence first.
+    import chunk_plan_oracle as po
+    cost = po.Model(alpha1=1.0, alpha2=0.0, beta1=0.0)
+    mem = model(d_p=2, d_s=1, layers=2)
+    meshes = {1: ([8], 64.0, 8), 2: ([6, 2], 36.0, 6)}
+    assert po.balanced_mesh_time(cost, 8, 2, 1) == 36.0 and po.balanced_mesh_time(cost, 8, 1, 1) == 64.0
+    K, t, chunks, groups = o.plan_batch(po, cost, mem, [8, 4, 4], [1, 2], 1.0 / 3.0, lambda k: meshes[k])
+    assert (K, t) == (2, 128.0)
+    assert chunks == [(0, [(0, 0, 6)], 1), (6, [(0, 6, 2), (1, 0, 4)], 0), (0, [(2, 0, 4)], 0)]
+    assert groups == [[[0, 1], [2]]]
+    # each K alone
+    assert o.plan_batch(po, cost, mem, [8, 4, 4], [1], 1.0 / 3.0, lambda k: meshes[k])[:2] == (1, 144.0)
+    assert o.plan_batch(po, cost, mem, [8, 4, 4], [2], 1.0 / 3.0, lambda k: meshes[k])[1] == 128.0
