@@ -1,6 +1,8 @@
 // Seeded random calls into the host-side planner and scheduler, meant to be built with -fsanitize=address,undefined:
 // checks memory safety and the structural guarantees of the outputs (no reference values are needed for that).
 #include <cstdio>
+#include <algorithm>
+#include <cstdint>
 #include <cstdlib>
 #include <random>
 #include <vector>
@@ -11,12 +13,84 @@
 
 #define REQUIRE(c) do { if (!(c)) { std::printf("FAILED %s at line %d (seed %u)\n", #c, __LINE__, seed); return 1; } } while (0)
 
+// The work items of the three attention kernels on a random segment table (contexts, gaps between key ranges, ragged
+// lengths): the (query row, key row) pairs an item list implies must be exactly the unmasked pairs of the chunk
+// (paper section 3.1: query i of a segment sees the keys j <= C + i of its own key range), each exactly once, no item
+// and no scheduled (query tile, key tile) without a visible pair.
+static int check_plan_cover(unsigned seed) {
+  std::mt19937 rng(seed * 2654435761u + 17);
+  auto uni = [&](int lo, int hi) { return (int)(rng() % (unsigned)(hi - lo + 1)) + lo; };
+  const int n_seg = uni(1, 6);
+  std::vector<chunk_attn_seg> segs(n_seg);
+  int32_t tq = 0, tkv = uni(0, 1) ? uni(0, 70) : 0;  // key rows before the first segment that nobody sees
+  for (auto& s : segs) {
+    const int q_len = uni(0, 3) ? uni(1, 200) : uni(1, 33);
+    const int ctx = uni(0, 2) ? 0 : uni(1, 300);
+    s = chunk_attn_seg{tq, q_len, tkv, ctx + q_len};
+    tq += q_len;
+    tkv += ctx + q_len + (uni(0, 3) ? 0 : uni(1, 40));  // sometimes a gap
+  }
+  chunk_attn_desc d{8, 2, 128, tq, tkv, n_seg, segs.data(), 0.1f};
+  REQUIRE(chunk_attn::validate(&d) == CHUNK_ATTN_OK);
+  std::vector<uint8_t> want((size_t)tq * tkv, 0);
+  int64_t n_pairs = 0;
+  for (const auto& s : segs)
+    for (int i = 0; i < s.q_len; ++i)
+      for (int j = 0; j <= s.kv_len - s.q_len + i; ++j) { want[(size_t)(s.q_start + i) * tkv + s.kv_start + j] = 1; ++n_pairs; }
+  REQUIRE(n_pairs == chunk_attn::pair_count(&d));
+  // a query tile of rows [q0, q0 + rows), row r seeing the first n0 + r keys from key row kv0, walked in key tiles of `bn`
+  auto cover_rows = [&](std::vector<uint8_t>& got, int q0, int rows, int kv0, int n0, int bn) -> bool {
+    if (rows < 1 || n0 < 1) return false;
+    const int n_last = n0 + rows - 1;
+    for (int t = 0; t * bn < n_last; ++t) {  // every key tile the kernels walk holds a visible pair of the last row
+      bool any = false;
+      for (int r = 0; r < rows; ++r)
+        for (int j = t * bn; j < std::min((t + 1) * bn, n0 + r); ++j) {
+          if (q0 + r >= tq || kv0 + j >= tkv) return false;
+          ++got[(size_t)(q0 + r) * tkv + kv0 + j];
+          any = true;
+        }
+      if (!any) return false;
+    }
+    return true;
+  };
+  for (int tile_rows : {32, 64, 128, 256}) {
+    std::vector<uint8_t> got((size_t)tq * tkv, 0);
+    for (const auto& it : chunk_attn::plan_fwd(&d, tile_rows)) REQUIRE(cover_rows(got, it.q_row0, it.q_rows, it.kv_row0, it.n0, 32));
+    REQUIRE(got == want);
+    std::fill(got.begin(), got.end(), 0);
+    for (const auto& it : chunk_attn::plan_dq(&d, tile_rows)) REQUIRE(cover_rows(got, it.q_row0, it.q_rows, it.kv_row0, it.n0, 32));
+    REQUIRE(got == want);
+  }
+  for (int keys : {32, 128}) {
+    std::vector<uint8_t> got((size_t)tq * tkv, 0);
+    for (const auto& it : chunk_attn::plan_dkv(&d, keys)) {
+      REQUIRE(it.kv_rows >= 1 && it.kv_rows <= keys && it.qt_first >= 0 && it.qt_first < it.n_qt);
+      REQUIRE(it.n_qt == (it.q_len + 31) / 32);
+      for (int qt = it.qt_first; qt < it.n_qt; ++qt) {  // the 32-row query tiles the kernel walks
+        bool any = false;
+        for (int i = 32 * qt; i < std::min(32 * qt + 32, it.q_len); ++i)
+          for (int kk = 0; kk < it.kv_rows; ++kk)
+            if (i >= it.j0 + kk - it.ctx) {  // query i of the segment sees key j0 + kk
+              REQUIRE(it.q_row_seg + i < tq && it.kv_row0 + kk < tkv);
+              ++got[(size_t)(it.q_row_seg + i) * tkv + it.kv_row0 + kk];
+              any = true;
+            }
+        REQUIRE(any);
+      }
+    }
+    REQUIRE(got == want);
+  }
+  return 0;
+}
+
 int main(int argc, char** argv) {
   const unsigned n_cases = argc > 1 ? (unsigned)std::atoi(argv[1]) : 200;
   int n_infeasible = 0, n_ckpt = 0;
   for (unsigned seed = 1; seed <= n_cases; ++seed) {
     std::mt19937 rng(seed);
     auto uni = [&](int lo, int hi) { return (int)(rng() % (unsigned)(hi - lo + 1)) + lo; };
+    if (check_plan_cover(seed)) return 1;
     // ---- sequence processor ----
     chunk_cost_model cm{1e-6 * uni(1, 50), 1e-3 * uni(0, 50), 1.0 * uni(0, 5), 1e-4 * uni(0, 3), 0.1 * uni(0, 3), uni(1, 8), uni(1, 4)};
     const int n_seqs = uni(1, 40), K = uni(1, 9), align = 1 << uni(0, 7);
