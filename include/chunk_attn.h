@@ -31,9 +31,15 @@
  * void*; NULL is the default stream) and return.  The segment table is a HOST pointer and
  * is only read during the call.  The library allocates no device memory: scratch space is
  * the caller's `workspace` (device memory, 256-byte aligned, at least the size reported by
- * chunk_attn_workspace_bytes).  Functions return CHUNK_ATTN_OK (0) or a negative code and
+ * chunk_attn_workspace_bytes).  Every tensor pointer must be 16-byte aligned (lse: 4-byte),
+ * else CHUNK_ATTN_INVALID_ARG.  Functions return CHUNK_ATTN_OK (0) or a negative code and
  * never throw or abort; argument errors are detected on the host before anything is
  * launched.
+ *
+ * The only state the library keeps between calls is a pool of pinned host buffers through
+ * which the tile schedules of chunk_attn_fwd / chunk_attn_bwd are uploaded (it grows with
+ * the schedules in flight, to 256 MB at most).  The library owns it; chunk_attn_shutdown
+ * releases it.
  */
 #ifndef CHUNK_ATTN_H_
 #define CHUNK_ATTN_H_
@@ -143,6 +149,23 @@ int64_t chunk_attn_pair_count(const chunk_attn_desc* desc);
  * The caller owns the events.  Always returns CHUNK_ATTN_OK.
  */
 int chunk_attn_profile_events(void* start_event, void* stop_event);
+
+/*
+ * Releases the pinned host buffers the library has allocated for schedule uploads (waiting for the
+ * uploads that still read them).  Optional: call it when no more work will be submitted, or to
+ * return the memory between phases; later calls simply allocate again.  Must not run concurrently
+ * with other calls of this library.  Returns CHUNK_ATTN_OK or CHUNK_ATTN_HIP_ERROR.
+ */
+int chunk_attn_shutdown(void);
+
+/*
+ * Test hook (not part of the method): the head_dim 128 forward keeps the softmax reference
+ * maximum of a row fixed after its first key tile and recomputes, in a second pass with a moving
+ * maximum, the rows whose later scores exceed it by more than 2^log2_growth (default 60; any
+ * reference gives the same softmax).  A very negative value sends every row through the second
+ * pass.  Process-wide.  Always returns CHUNK_ATTN_OK.
+ */
+int chunk_attn_test_set_fwd_rescale_limit(float log2_growth);
 
 /* Static description of an error code; for CHUNK_ATTN_HIP_ERROR includes the last HIP error text. */
 const char* chunk_attn_strerror(int code);

@@ -175,6 +175,18 @@ def chunk_attn_bwd_f32kv(desc, q, k, v, o, d_o, lse, dq, dk, dv, accumulate_dkv,
         raise ChunkAttnError(rc)
 
 
+def chunk_attn_shutdown() -> None:
+    """Releases the pinned staging buffers of the library (they are allocated again on demand)."""
+    rc = _lib.chunk_attn_shutdown()
+    if rc != 0:
+        raise ChunkAttnError(rc)
+
+
+def chunk_attn_test_set_fwd_rescale_limit(log2_growth: float) -> None:
+    """Test hook: growth of a row's maximum (log2) past which the head_dim 128 forward takes its second pass."""
+    _lib.chunk_attn_test_set_fwd_rescale_limit(ctypes.c_float(log2_growth))
+
+
 def chunk_attn_profile_events(start_event, stop_event) -> None:
     """Arms raw hipEvent_t handles (ints or None) for the next forward/backward call of this thread."""
     _lib.chunk_attn_profile_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))

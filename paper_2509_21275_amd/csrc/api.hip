@@ -1,6 +1,8 @@
 // C ABI of the chunk-attention library (include/chunk_attn.h): argument checks, workspace carving,
 // schedule upload and kernel launches.  No device memory is allocated here; the only memory the
-// library owns is a small ring of pinned host buffers through which tile schedules are uploaded.
+// library owns is a small ring of pinned host buffers through which tile schedules are uploaded
+// (released by chunk_attn_shutdown).
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -101,8 +103,30 @@ struct StagingRing {
     s->in_flight = true;
     return hipSuccess;
   }
+
+  // Waits for the uploads still reading the buffers and frees them all; the ring starts again from nothing.
+  hipError_t release() {
+    std::lock_guard<std::mutex> lock(mu);
+    hipError_t first = hipSuccess;
+    for (Slot& c : slots) {
+      hipError_t e = hipSuccess;
+      if (c.in_flight) e = hipEventSynchronize(c.ev);
+      if (e == hipSuccess && c.ev) e = hipEventDestroy(c.ev);
+      if (e == hipSuccess && c.host) e = hipHostFree(c.host);
+      if (e != hipSuccess && first == hipSuccess) first = e;
+    }
+    slots.clear();
+    next = total = 0;
+    return first;
+  }
 };
 StagingRing g_ring;
+
+// log2 growth of a row's maximum past the first key tile's at which the head_dim 128 forward hands the row to its
+// rescaling second pass: bf16 probabilities and fp32 sums hold 2^60 with room to spare
+std::atomic<float> g_fwd_rescale_limit{60.0f};
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // Forward workspace: [work items | transpose jobs | redo flags (zero)] (uploaded as one blob) then the
 // transposed V images.
@@ -131,7 +155,7 @@ void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_plan) {
   L.jobs_off = align_up(L.items_bytes);
   L.blocks = (int64_t)n_items * d->num_kv_heads * (group / heads_per_wg(group, fwd_waves(d->head_dim)));
   L.flags_off = align_up(L.jobs_off + (size_t)L.kv_tiles * sizeof(TileJob));
-  L.blob_bytes = L.flags_off + (size_t)L.blocks * sizeof(int32_t);
+  L.blob_bytes = L.flags_off + ((size_t)L.blocks + 1) * sizeof(int32_t);  // one flag per workgroup, then "any flag raised"
   L.vt_off = align_up(L.blob_bytes);
   L.total = L.vt_off + align_up((size_t)L.kv_tiles * d->num_kv_heads * d->head_dim * 64 * sizeof(__bf16));
 }
@@ -154,6 +178,16 @@ int chunk_attn_profile_events(void* start_event, void* stop_event) {
 }
 
 int chunk_attn_validate(const chunk_attn_desc* desc) { return validate(desc); }
+
+int chunk_attn_shutdown(void) {
+  const hipError_t e = g_ring.release();
+  return e == hipSuccess ? CHUNK_ATTN_OK : hip_fail(e, "releasing the staging buffers");
+}
+
+int chunk_attn_test_set_fwd_rescale_limit(float log2_growth) {
+  g_fwd_rescale_limit.store(log2_growth);
+  return CHUNK_ATTN_OK;
+}
 
 int64_t chunk_attn_pair_count(const chunk_attn_desc* desc) {
   const int rc = validate(desc);
@@ -199,6 +233,8 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   if (rc != CHUNK_ATTN_OK) return rc;
   if (!q || !k || !v || !o || !lse || !workspace) return CHUNK_ATTN_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return CHUNK_ATTN_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(lse) & 3) != 0)
+    return CHUNK_ATTN_INVALID_ARG;  // the kernels move rows in 16-byte pieces
   FwdLayout L;
   layout_fwd(desc, L, true);
   if (workspace_bytes < L.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
@@ -211,9 +247,6 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   hipError_t e = g_ring.upload(ws, blob.data(), blob.size(), stream);
   if (e != hipSuccess) return hip_fail(e, "schedule upload");
   __bf16* vt = reinterpret_cast<__bf16*>(ws + L.vt_off);
-  e = launch_transpose(static_cast<const __bf16*>(v), desc->num_kv_heads, desc->head_dim, 64,
-                       reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.jobs.size(), L.kv_tiles, vt, stream);
-  if (e != hipSuccess) return hip_fail(e, "transpose launch");
 
   FwdParams p;
   p.q = static_cast<const __bf16*>(q);
@@ -232,15 +265,14 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   p.total_q = desc->total_q;
   p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
   p.redo = desc->head_dim == 128 ? reinterpret_cast<int32_t*>(ws + L.flags_off) : nullptr;
-  // bf16 probabilities and fp32 sums hold 2^60 with room to spare; CHUNK_ATTN_FWD_REF_LIMIT overrides it (tests)
-  p.ref_limit = 60.0f;
-  if (const char* e = std::getenv("CHUNK_ATTN_FWD_REF_LIMIT")) p.ref_limit = (float)std::atof(e);
+  p.any_redo = reinterpret_cast<int32_t*>(ws + L.flags_off) + L.blocks;
+  p.ref_limit = g_fwd_rescale_limit.load();
   const int64_t blocks = L.blocks;
   if (blocks > 0x7fffffff) return CHUNK_ATTN_UNSUPPORTED;
   ProfileEvents pe = profile_events();
   profile_events() = ProfileEvents{};
   if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return hip_fail(e, "event record");
-  e = launch_fwd(p, desc->head_dim, (int)blocks, stream);
+  e = launch_fwd(p, desc->head_dim, (int)blocks, reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.jobs.size(), stream);
   if (e != hipSuccess) return hip_fail(e, "forward launch");
   if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return hip_fail(e, "event record");
   return CHUNK_ATTN_OK;
@@ -254,6 +286,9 @@ int bwd_any(const chunk_attn_desc* desc, const void* q, const void* k, const voi
   if (rc != CHUNK_ATTN_OK) return rc;
   if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return CHUNK_ATTN_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return CHUNK_ATTN_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) ||
+      !aligned16(dv) || (reinterpret_cast<uintptr_t>(lse) & 3) != 0)
+    return CHUNK_ATTN_INVALID_ARG;  // the kernels move rows in 16-byte pieces
   BwdPlan P;
   bwd_layout(desc, P, true);
   if (workspace_bytes < P.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
@@ -289,7 +324,6 @@ int chunk_attn_bwd(const chunk_attn_desc* desc, const void* q, const void* k, co
 int chunk_attn_bwd_f32kv(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
                          const void* d_o, const float* lse, void* dq, float* dk, float* dv, int accumulate_dkv,
                          void* workspace, size_t workspace_bytes, void* stream_v) {
-  if ((reinterpret_cast<uintptr_t>(dk) & 15) != 0 || (reinterpret_cast<uintptr_t>(dv) & 15) != 0) return CHUNK_ATTN_INVALID_ARG;
   return bwd_any(desc, q, k, v, o, d_o, lse, dq, dk, dv, true, accumulate_dkv, workspace, workspace_bytes, stream_v);
 }
 

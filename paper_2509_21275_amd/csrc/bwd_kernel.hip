@@ -1426,13 +1426,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
 // ------------------------------------------------------------------------------------------------
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
+// Raises a kernel's dynamic-LDS limit; callers keep the result in a function-local static, so that it happens once per
+// process and is safe from several threads.
 template <class K>
-hipError_t set_smem(K kernel, size_t smem, bool* done) {
-  if (*done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)smem);
-  if (e == hipSuccess) *done = true;
-  return e;
+hipError_t raise_smem_limit(K kernel, size_t smem) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
 }
 
 template <int D>
@@ -1478,17 +1476,18 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.heads_per_wg = heads_per_wg(group, dq_waves(D)); p.head_splits = group / p.heads_per_wg;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
-    static bool attr = false;
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if constexpr (D == 128) {
       const size_t smem = (size_t)2 * (DQ_PIPE_DIST + 3) * 32 * D * 2;  // ring slots of a K and a V tile
-      if ((e = set_smem(&bwd_dq_pipe_kernel<D>, smem, &attr)) != hipSuccess) return e;
+      static const hipError_t attr = raise_smem_limit(&bwd_dq_pipe_kernel<D>, smem);
+      if (attr != hipSuccess) return attr;
       hipLaunchKernelGGL((bwd_dq_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
     } else {
       const size_t smem = (size_t)9 * 32 * D * 2;  // 3 stages of K, V and K^T tiles
       constexpr int DQW = 4;
-      if ((e = set_smem(&bwd_dq_kernel<D, DQW>, smem, &attr)) != hipSuccess) return e;
+      static const hipError_t attr = raise_smem_limit(&bwd_dq_kernel<D, DQW>, smem);
+      if (attr != hipSuccess) return attr;
       hipLaunchKernelGGL((bwd_dq_kernel<D, DQW>), dim3((unsigned)blocks), dim3(DQW * 64), smem, stream, p);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1506,21 +1505,22 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     static_assert(DKV_KEYS == 128, "both kernels cover 128 keys per workgroup");
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    static bool attr = false;
     ProfileEvents pe = profile_events();
     profile_events() = ProfileEvents{};
     if constexpr (D == 128) {
       // ring slots of two 32-row operand tiles, 2 P hand-over slots, one slot of LSE and D rows per ring slot
       constexpr int NS = DKV_PIPE_DIST + 5;
       const size_t smem = (size_t)2 * NS * 32 * D * 2 + 2 * 4096 * 2 + 2 * NS * 64 * sizeof(float);
-      if ((e = set_smem(&bwd_dkv_pipe_kernel<D>, smem, &attr)) != hipSuccess) return e;
+      static const hipError_t attr = raise_smem_limit(&bwd_dkv_pipe_kernel<D>, smem);
+      if (attr != hipSuccess) return attr;
       if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
       hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
     } else {
       // 4 ring slots of two 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
       constexpr int KB = DKV_KEYS / 32;
       const size_t smem = (size_t)8 * 32 * D * 2 + 2 * KB * 1024 * 2 + 2 * 4 * 64 * sizeof(float);
-      if ((e = set_smem(&bwd_dkv_kernel<D, KB>, smem, &attr)) != hipSuccess) return e;
+      static const hipError_t attr = raise_smem_limit(&bwd_dkv_kernel<D, KB>, smem);
+      if (attr != hipSuccess) return attr;
       if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
       hipLaunchKernelGGL((bwd_dkv_kernel<D, KB>), dim3((unsigned)blocks), dim3(KB * 128), smem, stream, p);
     }

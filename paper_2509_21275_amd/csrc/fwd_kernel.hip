@@ -587,7 +587,10 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
     step(t, x[0], x[1], f[0], f[1], std::true_type{});
     step(t + 1, x[1], x[0], f[1], f[0], std::true_type{});
   }
-  if (__any(risk) && lane == 0) p.redo[blockIdx.x] = 1;
+  if (__any(risk) && lane == 0) {
+    p.redo[blockIdx.x] = 1;
+    *p.any_redo = 1;
+  }
 
   // ---- epilogue: O = O^T / l, LSE = ln(l) + m scale ----
 #pragma unroll
@@ -610,41 +613,38 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
   }
 }
 
-template <int D, int WAVES>
-static hipError_t launch_fwd_t(const FwdParams& p, int num_blocks, hipStream_t stream);
-
-static hipError_t launch_fwd_pipe(const FwdParams& p, int num_blocks, hipStream_t stream) {
-  const size_t smem = (size_t)2 * (FWD_PIPE_DIST + 3) * 32 * 128 * 2;  // ring slots of a K and a V tile
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_pipe_kernel<128>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((fwd_pipe_kernel<128>), dim3(num_blocks), dim3(256), smem, stream, p);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  // second pass over the same items, 8 waves of 32 rows: a workgroup returns at once unless its flag is raised
-  return launch_fwd_t<128, 8>(p, num_blocks, stream);
+// The dynamic-LDS limit of a kernel is raised once per process (thread-safe: a function-local static).
+template <class K>
+static hipError_t raise_smem_limit(K kernel, size_t smem) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
 }
 
 template <int D, int WAVES>
 static hipError_t launch_fwd_t(const FwdParams& p, int num_blocks, hipStream_t stream) {
   const size_t smem = (size_t)4 * 64 * D * 2;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_kernel<D, WAVES>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static const hipError_t attr = raise_smem_limit(&fwd_kernel<D, WAVES>, smem);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL((fwd_kernel<D, WAVES>), dim3(num_blocks), dim3(WAVES * 64), smem, stream, p);
   return hipGetLastError();
 }
 
-hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, hipStream_t stream) {
-  return head_dim == 128 ? launch_fwd_pipe(p, num_blocks, stream) : launch_fwd_t<64, 4>(p, num_blocks, stream);
+hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, const TileJob* vjobs, int num_vjobs, hipStream_t stream) {
+  hipError_t e;
+  if (head_dim != 128) {
+    if ((e = launch_transpose(p.v, p.num_kv_heads, head_dim, 64, vjobs, num_vjobs, p.total_kv_tiles, const_cast<__bf16*>(p.vt),
+                              stream)) != hipSuccess) return e;
+    return launch_fwd_t<64, 4>(p, num_blocks, stream);
+  }
+  const size_t smem = (size_t)2 * (FWD_PIPE_DIST + 3) * 32 * 128 * 2;  // ring slots of a K and a V tile
+  static const hipError_t attr = raise_smem_limit(&fwd_pipe_kernel<128>, smem);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL((fwd_pipe_kernel<128>), dim3(num_blocks), dim3(256), smem, stream, p);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // Second pass over the same items, 8 waves of 32 rows: a workgroup returns at once unless its flag is raised, and the
+  // transposed V images it reads are only made if any flag is.
+  if ((e = launch_transpose(p.v, p.num_kv_heads, head_dim, 64, vjobs, num_vjobs, p.total_kv_tiles, const_cast<__bf16*>(p.vt),
+                            stream, p.any_redo)) != hipSuccess) return e;
+  return launch_fwd_t<128, 8>(p, num_blocks, stream);
 }
 
 }  // namespace chunk_attn

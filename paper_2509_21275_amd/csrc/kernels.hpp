@@ -26,6 +26,7 @@ struct FwdParams {
   int32_t total_q;
   float scale_log2;                          // softmax scale * log2(e)
   int32_t* redo;                             // per-workgroup redo flags of the pipelined forward (null: run every item)
+  int32_t* any_redo;                         // raised together with any redo flag (gates the second pass's preparation)
   float ref_limit;                           // log2 growth of the row maximum past the first tile's that raises the flag
 };
 
@@ -80,11 +81,13 @@ std::vector<char> bwd_blob(const BwdPlan& plan);
 // Enqueues the backward kernels; the blob must already be on its way to the workspace on `stream`.
 hipError_t launch_bwd(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& plan, hipStream_t stream);
 
-hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, hipStream_t stream);
+// The forward kernels of one call.  `vjobs` (device) lists the 64-row tiles of V whose transposed images p.vt receives:
+// before the kernel for head_dim 64, after the pipelined kernel and only if it raised a redo flag for head_dim 128.
+hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, const TileJob* vjobs, int num_vjobs, hipStream_t stream);
 
 // Transposed tile images (width 64 or 32 rows) of x[rows][num_heads][head_dim]:
-// out[num_heads][total_tiles][head_dim][width].
+// out[num_heads][total_tiles][head_dim][width].  With a non-null `gate` (device) the kernel does nothing unless *gate != 0.
 hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, int width, const TileJob* jobs, int num_jobs,
-                            int64_t total_tiles, __bf16* out, hipStream_t stream);
+                            int64_t total_tiles, __bf16* out, hipStream_t stream, const int32_t* gate = nullptr);
 
 }  // namespace chunk_attn

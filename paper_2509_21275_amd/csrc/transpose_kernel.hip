@@ -14,7 +14,8 @@ namespace chunk_attn {
 template <int D, int W>
 __global__ __launch_bounds__(256) void transpose_tiles_kernel(const __bf16* __restrict__ x, int num_heads,
                                                               const TileJob* __restrict__ jobs, int64_t total_tiles,
-                                                              __bf16* __restrict__ out) {
+                                                              __bf16* __restrict__ out, const int32_t* __restrict__ gate) {
+  if (gate && *gate == 0) return;
   constexpr int P = D + 2;  // LDS pitch (elements) of the staging tile
   __shared__ __bf16 stage[W * P];
   const int tid = threadIdx.x;
@@ -45,20 +46,20 @@ __global__ __launch_bounds__(256) void transpose_tiles_kernel(const __bf16* __re
 
 template <int D, int W>
 static void launch_t(const __bf16* x, int num_heads, const TileJob* jobs, int64_t blocks, int64_t total_tiles,
-                     __bf16* out, hipStream_t stream) {
+                     __bf16* out, hipStream_t stream, const int32_t* gate) {
   hipLaunchKernelGGL((transpose_tiles_kernel<D, W>), dim3((unsigned)blocks), dim3(256), 0, stream, x, num_heads, jobs,
-                     total_tiles, out);
+                     total_tiles, out, gate);
 }
 
 hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, int width, const TileJob* jobs, int num_jobs,
-                            int64_t total_tiles, __bf16* out, hipStream_t stream) {
+                            int64_t total_tiles, __bf16* out, hipStream_t stream, const int32_t* gate) {
   if (num_jobs == 0) return hipSuccess;
   const int64_t blocks = (int64_t)num_jobs * num_heads;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-  if (head_dim == 128 && width == 64) launch_t<128, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream);
-  else if (head_dim == 128 && width == 32) launch_t<128, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream);
-  else if (head_dim == 64 && width == 64) launch_t<64, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream);
-  else if (head_dim == 64 && width == 32) launch_t<64, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream);
+  if (head_dim == 128 && width == 64) launch_t<128, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
+  else if (head_dim == 128 && width == 32) launch_t<128, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
+  else if (head_dim == 64 && width == 64) launch_t<64, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
+  else if (head_dim == 64 && width == 32) launch_t<64, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

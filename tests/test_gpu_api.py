@@ -96,3 +96,56 @@ def test_workspace_too_small_and_null_pointers_are_reported():
                             ctypes.c_void_p(o.data_ptr()), ctypes.c_void_p(lse.data_ptr()),
                             ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel()), None)
     assert rc == ca.INVALID_ARG
+
+
+def test_shutdown_releases_the_staging_buffers_and_later_calls_start_over():
+    """chunk_attn_shutdown frees the pinned upload buffers (waiting for uploads in flight); the next call allocates
+    again and gives the same bits."""
+    import paper_2509_21275_amd as ca
+    case = synth.scaled_case(3, 16)
+    q, k, v, do = make_inputs(case)
+    a = run_gpu(case, q, k, v, do)
+    ca.chunk_attn_shutdown()
+    ca.chunk_attn_shutdown()          # nothing left to free
+    b = run_gpu(case, q, k, v, do)
+    # shut down while a call's upload may still be in flight: the release waits for it
+    desc = ca.make_desc(case.segs, case.num_q_heads, case.num_kv_heads, case.head_dim, case.total_q, case.total_kv,
+                        case.scale)
+    ws = ca.alloc_workspace(desc)
+    o = torch.empty_like(q); lse = torch.empty((case.num_q_heads, case.total_q), dtype=torch.float32, device="cuda")
+    ca.chunk_attn_fwd(desc, q, k, v, o, lse, ws)
+    ca.chunk_attn_shutdown()
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    assert torch.equal(o, a[0]) and torch.equal(lse, a[1])
+
+
+def test_misaligned_tensor_pointers_are_rejected_on_the_host():
+    """Rows are moved in 16-byte pieces: a tensor pointer that is not 16-byte aligned is an argument error, found
+    before anything is launched."""
+    import ctypes
+    import paper_2509_21275_amd as ca
+    case = synth.scaled_case(2, 16)
+    q, k, v, do = make_inputs(case)
+    desc = ca.make_desc(case.segs, case.num_q_heads, case.num_kv_heads, case.head_dim, case.total_q, case.total_kv,
+                        case.scale)
+    o = torch.empty_like(q); lse = torch.empty((case.num_q_heads, case.total_q), dtype=torch.float32, device="cuda")
+    dq = torch.empty_like(q); dk = torch.empty_like(k); dv = torch.empty_like(v)
+    ws = ca.alloc_workspace(desc)
+    lib = ctypes.CDLL(ca.LIB_PATH)
+    lib.chunk_attn_fwd.restype = ctypes.c_int
+    lib.chunk_attn_bwd.restype = ctypes.c_int
+    P = lambda t, off=0: ctypes.c_void_p(t.data_ptr() + off)
+    wsz = ctypes.c_size_t(ws.numel())
+    for bad in range(4):   # q, k, v, o each 2 bytes off
+        args = [P(q), P(k), P(v), P(o)]
+        args[bad] = P([q, k, v, o][bad], 2)
+        assert lib.chunk_attn_fwd(ctypes.byref(desc), *args, P(lse), P(ws), wsz, None) == ca.INVALID_ARG
+    for bad in range(8):   # q, k, v, o, d_o, dq, dk, dv
+        ts = [q, k, v, o, do, None, dq, dk, dv]
+        args = [P(t) if t is not None else P(lse) for t in ts]
+        i = bad if bad < 5 else bad + 1
+        args[i] = P(ts[i], 8)
+        assert lib.chunk_attn_bwd(ctypes.byref(desc), *args, ctypes.c_int(0), P(ws), wsz, None) == ca.INVALID_ARG
+    torch.cuda.synchronize()

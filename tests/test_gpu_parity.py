@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import synth
+import paper_2509_21275_amd as ca
 from gpu_util import TOL_GRAD, TOL_O, make_inputs, rel_err, run_gpu
 
 pytestmark = pytest.mark.gpu
@@ -86,13 +87,16 @@ def _forward_only(oracle_mod, case, q, k, v):
     return rel_err(o, O), float(np.abs(lse.double().cpu().numpy() - LSE).max())
 
 
-def test_forward_second_pass_forced(oracle_mod, monkeypatch):
+def test_forward_second_pass_forced(oracle_mod):
     """The head_dim-128 forward keeps one reference maximum per row and hands rows whose scores outgrow it to a
     second, rescaling pass.  With the growth limit set below any score every item takes the second pass."""
     case = synth.ChunkCase("redo_forced", synth.hybrid_chunk(200, 500, [130, 70]), 400, 900, 8, 2, 128, 31)
     q, k, v, _ = make_inputs(case)
-    monkeypatch.setenv("CHUNK_ATTN_FWD_REF_LIMIT", "-1e30")
-    eo, el = _forward_only(oracle_mod, case, q, k, v)
+    ca.chunk_attn_test_set_fwd_rescale_limit(-1e30)
+    try:
+        eo, el = _forward_only(oracle_mod, case, q, k, v)
+    finally:
+        ca.chunk_attn_test_set_fwd_rescale_limit(60.0)
     print("forced second pass", eo, el, flush=True)
     assert eo <= TOL_O and el <= 2e-2
 

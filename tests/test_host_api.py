@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol(ca):
         header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
         names |= set(re.findall(r"\b((?:chunk_attn|chunk_plan|chunk_sched|fused_ce)_[a-z0-9_]+)\s*\(", header))
     assert {"chunk_attn_fwd", "chunk_attn_bwd", "chunk_attn_bwd_f32kv", "chunk_attn_workspace_bytes", "chunk_attn_validate",
-            "chunk_attn_pair_count", "chunk_attn_strerror", "chunk_attn_profile_events",
+            "chunk_attn_pair_count", "chunk_attn_strerror", "chunk_attn_profile_events", "chunk_attn_shutdown",
+            "chunk_attn_test_set_fwd_rescale_limit",
             "chunk_plan_time", "chunk_plan_mesh", "chunk_plan_build", "chunk_plan_segments", "fused_ce_inplace",
             "chunk_sched_act_bytes", "chunk_sched_f2b", "chunk_sched_windows", "chunk_sched_solve_ckpt", "chunk_sched_group",
             "chunk_sched_simulate", "chunk_sched_plan_batch"} <= names
@@ -84,6 +85,14 @@ def test_null_descriptor_and_messages(ca):
     assert lib.chunk_attn_validate(None) == ca.INVALID_ARG
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(ca.chunk_attn_strerror(code), str) and ca.chunk_attn_strerror(code)
+
+
+def test_shutdown_without_any_upload_is_a_no_op(ca):
+    # nothing has been uploaded in this process: there is nothing to release, and no GPU call is made
+    lib = ctypes.CDLL(ca.LIB_PATH)
+    assert lib.chunk_attn_shutdown() == ca.OK
+    assert lib.chunk_attn_shutdown() == ca.OK
+    ca.chunk_attn_shutdown()
 
 
 def test_synthetic_workloads_have_the_documented_shapes():
