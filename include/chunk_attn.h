@@ -57,7 +57,8 @@ enum {
   CHUNK_ATTN_UNSUPPORTED = -2,         /* head_dim not 64 or 128, or num_q_heads % num_kv_heads != 0 */
   CHUNK_ATTN_BAD_SEGMENT = -3,         /* see chunk_attn_desc.segments */
   CHUNK_ATTN_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes below chunk_attn_workspace_bytes */
-  CHUNK_ATTN_HIP_ERROR = -5            /* a HIP call or kernel launch failed */
+  CHUNK_ATTN_HIP_ERROR = -5,           /* a HIP call or kernel launch failed */
+  CHUNK_ATTN_TOO_LARGE = -6            /* chunk_attn_fwd_static: more than its fixed scratch buffer holds */
 };
 
 /* One segment, in rows.  Context length C = kv_len - q_len >= 0. */
@@ -101,6 +102,21 @@ int chunk_attn_validate(const chunk_attn_desc* desc);
  */
 int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * chunk_attn_fwd for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and
+ * results as chunk_attn_fwd; the call allocates nothing, on the host side of the runtime or the
+ * device (no hipMalloc / hipFree / pinned buffers: the schedule is built by a small kernel from the
+ * segment table, which travels as a kernel argument).  Its scratch memory is a fixed array of
+ * 16 MiB inside the library, one copy per GPU, held until the process ends.
+ * Limits: at most 64 segments, and a forward scratch need (chunk_attn_workspace_bytes' *fwd_bytes:
+ * the schedule plus one transposed copy of V) of at most 16 MiB, else CHUNK_ATTN_TOO_LARGE and
+ * nothing is launched.  All calls on one GPU share that GPU's array: calls that may overlap on
+ * one GPU (different streams, different threads) race and must be serialised by the caller.
+ */
+int chunk_attn_fwd_static(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse,
+                          void* stream);
 
 /*
  * Backward for the loss L = sum(o .* d_o): dq for every query row; dk, dv for every

@@ -13,7 +13,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libchunk_attn.so")
 
-OK, INVALID_ARG, UNSUPPORTED, BAD_SEGMENT, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, -1, -2, -3, -4, -5
+OK, INVALID_ARG, UNSUPPORTED, BAD_SEGMENT, WORKSPACE_TOO_SMALL, HIP_ERROR, TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
 
 
 class Seg(ctypes.Structure):
@@ -50,6 +50,10 @@ def _load():
     lib.chunk_attn_workspace_bytes.restype = ctypes.c_int
     lib.chunk_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.chunk_attn_fwd.restype = ctypes.c_int
+    lib.chunk_attn_fwd_static.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    lib.chunk_attn_fwd_static.restype = ctypes.c_int
+    lib.chunk_attn_shutdown.restype = ctypes.c_int
+    lib.chunk_attn_test_set_fwd_rescale_limit.argtypes = [ctypes.c_float]
     lib.chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
     lib.chunk_attn_bwd.restype = ctypes.c_int
     lib.chunk_attn_bwd_f32kv.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
@@ -135,6 +139,18 @@ def chunk_attn_fwd(desc, q, k, v, o, lse, workspace, stream=None) -> None:
     _check(o, torch.bfloat16, qs, "o"); _check(lse, torch.float32, (desc.num_q_heads, desc.total_q), "lse")
     rc = _lib.chunk_attn_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(workspace),
                              workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != OK:
+        raise ChunkAttnError(rc)
+
+
+def chunk_attn_fwd_static(desc, q, k, v, o, lse, stream=None) -> None:
+    """chunk_attn_fwd without a workspace: the library's fixed per-GPU scratch array is used (small chunks only)."""
+    import torch
+    qs = (desc.total_q, desc.num_q_heads, desc.head_dim)
+    ks = (desc.total_kv, desc.num_kv_heads, desc.head_dim)
+    _check(q, torch.bfloat16, qs, "q"); _check(k, torch.bfloat16, ks, "k"); _check(v, torch.bfloat16, ks, "v")
+    _check(o, torch.bfloat16, qs, "o"); _check(lse, torch.float32, (desc.num_q_heads, desc.total_q), "lse")
+    rc = _lib.chunk_attn_fwd_static(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _stream(stream))
     if rc != OK:
         raise ChunkAttnError(rc)
 

@@ -160,6 +160,76 @@ void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_plan) {
   L.total = L.vt_off + align_up((size_t)L.kv_tiles * d->num_kv_heads * d->head_dim * 64 * sizeof(__bf16));
 }
 
+// ---- the forward that allocates nothing (chunk_attn_fwd_static) ----
+// Its scratch memory is this array instead of a caller's workspace: every GPU the library runs on holds its own copy, at
+// its own address, until the process ends.  Host code never uses the array's name as an address: static_scratch() asks
+// the runtime for the device address once per device and hands that out.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+constexpr int kStaticMaxSegments = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[64] = {};  // per device
+
+hipError_t static_scratch(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if ((e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = static_cast<char*>(g_scratch_ptr[dev]);
+  return hipSuccess;
+}
+
+// The forward's schedule made on the device from a segment table passed by value: work items in segment order (their
+// order does not change any result), the 64-row tiles of V, and the redo flags cleared.
+struct StaticSegs {
+  chunk_attn_seg seg[kStaticMaxSegments];
+};
+__global__ __launch_bounds__(256) void plan_fwd_static_kernel(StaticSegs segs, int n_seg, int tile_rows, FwdItem* items,
+                                                              int n_items, TileJob* jobs, int n_jobs, int32_t* flags,
+                                                              int n_flags) {
+  __shared__ int item0[kStaticMaxSegments + 1], job0[kStaticMaxSegments + 1];
+  if (threadIdx.x == 0) {
+    int ni = 0, nj = 0;
+    for (int t = 0; t < n_seg; ++t) {
+      item0[t] = ni;
+      job0[t] = nj;
+      ni += (segs.seg[t].q_len + tile_rows - 1) / tile_rows;
+      nj += (segs.seg[t].kv_len + 63) / 64;
+    }
+    item0[n_seg] = ni;
+    job0[n_seg] = nj;
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < n_items; x += 256) {
+    int t = 0;
+    while (t + 1 < n_seg && item0[t + 1] <= x) ++t;
+    const chunk_attn_seg s = segs.seg[t];
+    const int i0 = (x - item0[t]) * tile_rows;
+    FwdItem it{};
+    it.q_row0 = s.q_start + i0;
+    it.q_rows = min(tile_rows, s.q_len - i0);
+    it.kv_row0 = s.kv_start;
+    it.n0 = s.kv_len - s.q_len + i0 + 1;
+    it.kv_tile0 = job0[t];
+    items[x] = it;
+  }
+  for (int x = threadIdx.x; x < n_jobs; x += 256) {
+    int t = 0;
+    while (t + 1 < n_seg && job0[t + 1] <= x) ++t;
+    const chunk_attn_seg s = segs.seg[t];
+    const int r = (x - job0[t]) * 64;
+    jobs[x] = TileJob{s.kv_start + r, min(64, s.kv_len - r), x, 0};
+  }
+  for (int x = threadIdx.x; x < n_flags; x += 256) flags[x] = 0;
+}
+
 }  // namespace
 
 namespace chunk_attn {
@@ -202,6 +272,9 @@ const char* chunk_attn_strerror(int code) {
     case CHUNK_ATTN_UNSUPPORTED: return "unsupported shape (head_dim must be 64 or 128; num_kv_heads must divide num_q_heads)";
     case CHUNK_ATTN_BAD_SEGMENT: return "bad segment table";
     case CHUNK_ATTN_WORKSPACE_TOO_SMALL: return "workspace too small (see chunk_attn_workspace_bytes)";
+    case CHUNK_ATTN_TOO_LARGE:
+      return "chunk too large for chunk_attn_fwd_static (at most 64 segments and 16 MiB of forward scratch, see "
+             "chunk_attn_workspace_bytes); use chunk_attn_fwd with a workspace";
     case CHUNK_ATTN_HIP_ERROR: {
       static thread_local std::string msg;
       msg = "HIP error: " + g_last_hip_error;
@@ -275,6 +348,54 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   e = launch_fwd(p, desc->head_dim, (int)blocks, reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.jobs.size(), stream);
   if (e != hipSuccess) return hip_fail(e, "forward launch");
   if (pe.stop && (e = hipEventRecord(pe.stop, stream)) != hipSuccess) return hip_fail(e, "event record");
+  return CHUNK_ATTN_OK;
+}
+
+int chunk_attn_fwd_static(const chunk_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse,
+                          void* stream_v) {
+  const int rc = validate(desc);
+  if (rc != CHUNK_ATTN_OK) return rc;
+  if (!q || !k || !v || !o || !lse) return CHUNK_ATTN_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(lse) & 3) != 0)
+    return CHUNK_ATTN_INVALID_ARG;
+  FwdLayout L;
+  layout_fwd(desc, L, false);
+  if (desc->num_segments > kStaticMaxSegments || L.total > kStaticScratchBytes || L.blocks > 0x7fffffff)
+    return CHUNK_ATTN_TOO_LARGE;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  char* ws = nullptr;
+  hipError_t e = static_scratch(&ws);
+  if (e != hipSuccess) return hip_fail(e, "address of the static scratch buffer");
+
+  StaticSegs segs;
+  for (int t = 0; t < desc->num_segments; ++t) segs.seg[t] = desc->segments[t];
+  const int n_items = (int)(L.items_bytes / sizeof(FwdItem));
+  hipLaunchKernelGGL(plan_fwd_static_kernel, dim3(1), dim3(256), 0, stream, segs, desc->num_segments, L.tile_rows,
+                     reinterpret_cast<FwdItem*>(ws), n_items, reinterpret_cast<TileJob*>(ws + L.jobs_off), (int)L.kv_tiles,
+                     reinterpret_cast<int32_t*>(ws + L.flags_off), (int)L.blocks + 1);
+  if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "schedule kernel launch");
+
+  FwdParams p;
+  p.q = static_cast<const __bf16*>(q);
+  p.k = static_cast<const __bf16*>(k);
+  p.v = static_cast<const __bf16*>(v);
+  p.o = static_cast<__bf16*>(o);
+  p.lse = lse;
+  p.vt = reinterpret_cast<__bf16*>(ws + L.vt_off);
+  p.items = reinterpret_cast<const FwdItem*>(ws);
+  p.total_kv_tiles = L.kv_tiles;
+  p.num_q_heads = desc->num_q_heads;
+  p.num_kv_heads = desc->num_kv_heads;
+  p.group = desc->num_q_heads / desc->num_kv_heads;
+  p.heads_per_wg = heads_per_wg(p.group, fwd_waves(desc->head_dim));
+  p.head_splits = p.group / p.heads_per_wg;
+  p.total_q = desc->total_q;
+  p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
+  p.redo = desc->head_dim == 128 ? reinterpret_cast<int32_t*>(ws + L.flags_off) : nullptr;
+  p.any_redo = reinterpret_cast<int32_t*>(ws + L.flags_off) + L.blocks;
+  p.ref_limit = g_fwd_rescale_limit.load();
+  e = launch_fwd(p, desc->head_dim, (int)L.blocks, reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.kv_tiles, stream);
+  if (e != hipSuccess) return hip_fail(e, "forward launch");
   return CHUNK_ATTN_OK;
 }
 
