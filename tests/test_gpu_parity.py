@@ -31,9 +31,9 @@ def test_config1_packed_full(oracle_mod):
     full_compare(oracle_mod, synth.case_by_index(1))
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
 def test_scaled_replicas_full(oracle_mod, idx):
-    full_compare(oracle_mod, synth.scaled_case(idx, 16))
+    full_compare(oracle_mod, synth.scaled_case(idx, 16))      # 5: the last slice of the long split sequence
 
 
 EDGE = [
