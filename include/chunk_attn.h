@@ -183,6 +183,23 @@ int chunk_attn_shutdown(void);
  */
 int chunk_attn_test_set_fwd_rescale_limit(float log2_growth);
 
+/*
+ * Test and measurement hook: which backward chunk_attn_bwd / chunk_attn_bwd_f32kv run for head_dim 128.
+ * 0: the library's choice; 1: two kernels (dQ query-stationary, dK/dV key-stationary, P recomputed in both);
+ * 2: one pass (the key-stationary kernel also forms dQ and adds it into float32 tiles in the workspace in a fixed
+ * order).  Same results up to the order of float32 additions in dQ; both are bit-reproducible.  Process-wide; the
+ * workspace size does not depend on it.  Returns CHUNK_ATTN_INVALID_ARG for any other value.
+ */
+int chunk_attn_test_set_bwd_mode(int mode);
+
+/*
+ * Test hook: byte offset, inside the backward workspace of `desc`, of the status word (uint32) of the one-pass
+ * backward.  After a head_dim 128 backward in mode 2 has completed it is 0 unless something went wrong: bit 0 = a wave
+ * gave up waiting for the workgroup before it in the dQ order (bounded wait; dQ is then wrong), bit 1 = a workgroup
+ * ran on another XCD than its index implies (the ordered updates then do not meet in one L2).
+ */
+int chunk_attn_test_bwd_status_offset(const chunk_attn_desc* desc, size_t* offset);
+
 /* Static description of an error code; for CHUNK_ATTN_HIP_ERROR includes the last HIP error text. */
 const char* chunk_attn_strerror(int code);
 

@@ -203,6 +203,24 @@ def chunk_attn_test_set_fwd_rescale_limit(log2_growth: float) -> None:
     _lib.chunk_attn_test_set_fwd_rescale_limit(ctypes.c_float(log2_growth))
 
 
+def chunk_attn_test_set_bwd_mode(mode: int) -> None:
+    """Test hook: 0 = library's choice, 1 = two-kernel backward, 2 = one-pass backward (head_dim 128)."""
+    rc = _lib.chunk_attn_test_set_bwd_mode(ctypes.c_int(mode))
+    if rc != 0:
+        raise ChunkAttnError(rc)
+
+
+def chunk_attn_test_bwd_status(desc, workspace) -> int:
+    """Test hook: the status word the one-pass backward left in `workspace` (synchronises the device)."""
+    import torch
+    off = ctypes.c_size_t(0)
+    rc = _lib.chunk_attn_test_bwd_status_offset(ctypes.byref(desc), ctypes.byref(off))
+    if rc != 0:
+        raise ChunkAttnError(rc)
+    torch.cuda.synchronize()
+    return int(workspace[off.value:off.value + 4].view(torch.int32).item())
+
+
 def chunk_attn_profile_events(start_event, stop_event) -> None:
     """Arms raw hipEvent_t handles (ints or None) for the next forward/backward call of this thread."""
     _lib.chunk_attn_profile_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))

@@ -126,6 +126,8 @@ StagingRing g_ring;
 // rescaling second pass: bf16 probabilities and fp32 sums hold 2^60 with room to spare
 std::atomic<float> g_fwd_rescale_limit{60.0f};
 
+std::atomic<int> g_bwd_mode{0};
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // Forward workspace: [work items | transpose jobs | redo flags (zero)] (uploaded as one blob) then the
@@ -233,6 +235,7 @@ __global__ __launch_bounds__(256) void plan_fwd_static_kernel(StaticSegs segs, i
 }  // namespace
 
 namespace chunk_attn {
+int bwd_mode() { return g_bwd_mode.load(); }
 ProfileEvents& profile_events() {
   static thread_local ProfileEvents ev;
   return ev;
@@ -252,6 +255,22 @@ int chunk_attn_validate(const chunk_attn_desc* desc) { return validate(desc); }
 int chunk_attn_shutdown(void) {
   const hipError_t e = g_ring.release();
   return e == hipSuccess ? CHUNK_ATTN_OK : hip_fail(e, "releasing the staging buffers");
+}
+
+int chunk_attn_test_set_bwd_mode(int mode) {
+  if (mode < 0 || mode > 2) return CHUNK_ATTN_INVALID_ARG;
+  g_bwd_mode.store(mode);
+  return CHUNK_ATTN_OK;
+}
+
+int chunk_attn_test_bwd_status_offset(const chunk_attn_desc* desc, size_t* offset) {
+  const int rc = validate(desc);
+  if (rc != CHUNK_ATTN_OK) return rc;
+  if (!offset) return CHUNK_ATTN_INVALID_ARG;
+  BwdPlan P;
+  bwd_layout(desc, P, false);
+  *offset = P.fprog_off + P.fprog_bytes - kFusedSinkBytes - 256;
+  return CHUNK_ATTN_OK;
 }
 
 int chunk_attn_test_set_fwd_rescale_limit(float log2_growth) {

@@ -1425,6 +1425,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
 // host side
 // ------------------------------------------------------------------------------------------------
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+size_t n_dkv_blocks(const chunk_attn_desc* d) {
+  size_t n = 0;
+  for (int t = 0; t < d->num_segments; ++t) n += (d->segments[t].kv_len + dkv_keys(d->head_dim) - 1) / dkv_keys(d->head_dim);
+  return n;
+}
 
 // Raises a kernel's dynamic-LDS limit; callers keep the result in a function-local static, so that it happens once per
 // process and is safe from several threads.
@@ -1468,6 +1473,9 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
   }
 
   const int group = d->num_q_heads / d->num_kv_heads;
+  if constexpr (D == 128) {
+    if (P.fused) return launch_bwd_fused(d, a, P, lse2p, dsp, stream);
+  }
   {  // dQ
     DqParams p;
     p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.kt = kt; p.lse2p = lse2p; p.dsp = dsp; p.dq = a.dq;
@@ -1537,32 +1545,46 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   const int dq_rows = tile_rows(group, dq_waves(d->head_dim));
   P.q_tiles = count_tiles(d, false, 64);
   P.kv32_tiles = count_tiles(d, true, 32);
+  P.qt32_tiles = count_tiles(d, false, 32);
+  P.fused = d->head_dim == 128 && bwd_mode() == 2;
   size_t n_dq = 0, n_dkv = 0;
   if (with_plan) {
-    P.dq_items = plan_dq(d, dq_rows);
-    P.dkv_items = plan_dkv(d, dkv_keys(d->head_dim));
+    if (P.fused) {
+      P.fplan = plan_fused(d, dkv_keys(d->head_dim), kNumXcd, fused_num_bufs(d, dkv_keys(d->head_dim)));
+    } else {
+      P.dq_items = plan_dq(d, dq_rows);
+      P.dkv_items = plan_dkv(d, dkv_keys(d->head_dim));
+    }
     P.qjobs = tile_jobs(d, false, 64, nullptr);
     P.kjobs = tile_jobs(d, true, 32, nullptr);
-    n_dq = P.dq_items.size();
-    n_dkv = P.dkv_items.size();
-  } else {
-    for (int t = 0; t < d->num_segments; ++t) {
-      n_dq += (d->segments[t].q_len + dq_rows - 1) / dq_rows;
-      n_dkv += (d->segments[t].kv_len + dkv_keys(d->head_dim) - 1) / dkv_keys(d->head_dim);
-    }
+  }
+  // the layout does not depend on which backward runs: item counts follow from the segment table
+  for (int t = 0; t < d->num_segments; ++t) {
+    n_dq += (d->segments[t].q_len + dq_rows - 1) / dq_rows;
+    n_dkv += (d->segments[t].kv_len + dkv_keys(d->head_dim) - 1) / dkv_keys(d->head_dim);
   }
   P.dq_items_off = 0;
   P.dkv_items_off = up256(n_dq * sizeof(DqItem));
   P.qjobs_off = P.dkv_items_off + up256(n_dkv * sizeof(DkvItem));
   P.kjobs_off = P.qjobs_off + up256((size_t)P.q_tiles * sizeof(TileJob));
-  P.blob_bytes = P.kjobs_off + up256((size_t)P.kv32_tiles * sizeof(TileJob));
+  P.fitems_off = P.kjobs_off + up256((size_t)P.kv32_tiles * sizeof(TileJob));
+  // the workspace is sized for either backward (the mode may change between the size query and the call): the one-pass
+  // backward has one item per (key block, key/value head) and at most 8 x that many workgroup slots
+  const size_t n_fused = d->head_dim == 128 ? n_dkv_blocks(d) * (size_t)d->num_kv_heads : 0;
+  P.forder_off = P.fitems_off + up256(n_fused * sizeof(FusedItem));
+  P.q32jobs_off = P.forder_off + up256(n_fused * kNumXcd * sizeof(int32_t));
+  P.blob_bytes = P.q32jobs_off + (d->head_dim == 128 ? up256((size_t)P.qt32_tiles * sizeof(DqTileJob)) : 0);
   const size_t row_slots = (size_t)d->num_q_heads * P.q_tiles * 64;
-  P.lse2p_off = P.blob_bytes;
+  P.fprog_off = P.blob_bytes;
+  // progress counters, then the status word (its own 256 bytes), then a scratch tile
+  P.fprog_bytes = up256(n_fused * 4 * sizeof(unsigned)) + 256 + kFusedSinkBytes;
+  P.lse2p_off = P.fprog_off + P.fprog_bytes;
   P.dsp_off = P.lse2p_off + up256(row_slots * sizeof(float));
   P.kt_off = P.dsp_off + up256(row_slots * sizeof(float));
   // transposed K images only for head_dim 64 (the head_dim 128 dQ kernel reads K^T from its K tiles)
   // (256 bytes remain in any case: the dK/dV kernels copy the LSE / D rows 64 at a time, up to 32 past a segment's last)
-  P.total = P.kt_off + (d->head_dim == 128 ? 256 : up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16)));
+  P.fdq_off = P.kt_off + (d->head_dim == 128 ? 256 : up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16)));
+  P.total = P.fdq_off + (d->head_dim == 128 ? (size_t)fused_num_bufs(d, dkv_keys(128)) * d->num_q_heads * P.qt32_tiles * 4096 * sizeof(float) : 0);
 }
 
 std::vector<char> bwd_blob(const BwdPlan& P) {
@@ -1571,6 +1593,11 @@ std::vector<char> bwd_blob(const BwdPlan& P) {
   std::memcpy(blob.data() + P.dkv_items_off, P.dkv_items.data(), P.dkv_items.size() * sizeof(DkvItem));
   std::memcpy(blob.data() + P.qjobs_off, P.qjobs.data(), P.qjobs.size() * sizeof(TileJob));
   std::memcpy(blob.data() + P.kjobs_off, P.kjobs.data(), P.kjobs.size() * sizeof(TileJob));
+  if (P.fused) {
+    std::memcpy(blob.data() + P.fitems_off, P.fplan.items.data(), P.fplan.items.size() * sizeof(FusedItem));
+    std::memcpy(blob.data() + P.forder_off, P.fplan.order.data(), P.fplan.order.size() * sizeof(int32_t));
+    std::memcpy(blob.data() + P.q32jobs_off, P.fplan.tiles.data(), P.fplan.tiles.size() * sizeof(DqTileJob));
+  }
   return blob;
 }
 

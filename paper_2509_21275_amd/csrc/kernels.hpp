@@ -73,7 +73,20 @@ struct BwdPlan {
   int64_t q_tiles = 0, kv32_tiles = 0;
   size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, blob_bytes = 0;
   size_t lse2p_off = 0, dsp_off = 0, kt_off = 0, total = 0;
+  // one-pass backward (head_dim 128): its items and workgroup order travel at the end of the blob; then the per-wave
+  // progress counters and the status word (cleared by a kernel on every call) and the float32 dQ tiles
+  bool fused = false;
+  FusedPlan fplan;
+  int64_t qt32_tiles = 0;
+  size_t fitems_off = 0, forder_off = 0, q32jobs_off = 0, fprog_off = 0, fprog_bytes = 0, fdq_off = 0;
 };
+constexpr size_t kFusedSinkBytes = 64 * 16384;  // scratch dQ tiles of the one-pass backward, behind its status word
+constexpr int kNumXcd = 8;  // XCDs of an MI355X: workgroup b runs on XCD b % 8
+
+// 0: the library's choice, 1: the two-kernel backward, 2: the one-pass backward (head_dim 128 only)
+int bwd_mode();
+hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& plan, const float* lse2p, const float* dsp,
+                            hipStream_t stream);
 // Fills the offsets (and, if with_plan, the schedules) for a validated descriptor.
 void bwd_layout(const chunk_attn_desc* d, BwdPlan& plan, bool with_plan);
 // The host image of the blob at the start of the workspace.

@@ -139,6 +139,82 @@ std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys) {
   return items;
 }
 
+int fused_num_bufs(const chunk_attn_desc* d, int keys) {
+  int most = 0;
+  for (int t = 0; t < d->num_segments; ++t) most = std::max(most, (d->segments[t].kv_len + keys - 1) / keys);
+  return most >= 64 ? 4 : most >= 16 ? 2 : 1;
+}
+
+FusedPlan plan_fused(const chunk_attn_desc* d, int keys, int num_xcd, int num_bufs) {
+  FusedPlan P;
+  P.num_bufs = num_bufs;
+  struct Chain { int first_item, n_items; int64_t work; };
+  std::vector<Chain> chains;
+  int32_t q_tile0 = 0, dq_tile0 = 0;
+  for (int t = 0; t < d->num_segments; ++t) {
+    const chunk_attn_seg& s = d->segments[t];
+    const int32_t C = s.kv_len - s.q_len;
+    const int32_t n_qt = (s.q_len + 31) / 32;
+    for (int kvh = 0; kvh < d->num_kv_heads; ++kvh) {
+      Chain ch{(int)P.items.size(), 0, 0};
+      int32_t b = 0;
+      for (int32_t j0 = 0; j0 < s.kv_len; j0 += keys, ++b) {
+        FusedItem it{};
+        it.kv_row0 = s.kv_start + j0;
+        it.kv_rows = std::min<int32_t>(keys, s.kv_len - j0);
+        it.j0 = j0;
+        it.ctx = C;
+        it.q_row_seg = s.q_start;
+        it.q_len = s.q_len;
+        it.qt_first = std::max<int32_t>(0, j0 - C) / 32;
+        it.n_qt = n_qt;
+        it.q_tile0 = q_tile0;
+        it.kvh = kvh;
+        it.buf = b % num_bufs;
+        it.pred = b < num_bufs ? -1 : (int32_t)P.items.size() - num_bufs;   // the block num_bufs before it: same sub-chain
+        it.delta_qt = b < num_bufs ? 0 : it.qt_first - P.items[it.pred].qt_first;
+        it.dq_tile0 = dq_tile0;
+        ch.work += n_qt - it.qt_first;
+        ++ch.n_items;
+        P.items.push_back(it);
+      }
+      chains.push_back(ch);
+    }
+    for (int32_t qt = 0; qt < n_qt; ++qt)
+      P.tiles.push_back(DqTileJob{s.q_start + 32 * qt, std::min<int32_t>(32, s.q_len - 32 * qt), dq_tile0 + qt, qt, C,
+                                  (s.kv_len + keys - 1) / keys, 0, 0});
+    q_tile0 += (s.q_len + 63) / 64;
+    dq_tile0 += n_qt;
+  }
+  P.total_qt32 = dq_tile0;
+  // chains to XCDs: most work first, each to the XCD with the least work so far
+  std::vector<int> by_work(chains.size());
+  for (size_t i = 0; i < chains.size(); ++i) by_work[i] = (int)i;
+  std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return chains[a].work > chains[b].work; });
+  std::vector<int64_t> load(num_xcd, 0);
+  std::vector<std::vector<int32_t>> lists(num_xcd);
+  for (int c : by_work) {
+    int x = 0;
+    for (int i = 1; i < num_xcd; ++i)
+      if (load[i] < load[x]) x = i;
+    load[x] += chains[c].work;
+    for (int i = 0; i < chains[c].n_items; ++i) lists[x].push_back(chains[c].first_item + i);
+  }
+  // inside an XCD: longest walk first; the walks of a chain do not grow along it, and the sort is stable, so a block
+  // always comes after its predecessor
+  size_t longest = 0;
+  for (auto& l : lists) {
+    std::stable_sort(l.begin(), l.end(), [&](int32_t a, int32_t b) {
+      return P.items[a].n_qt - P.items[a].qt_first > P.items[b].n_qt - P.items[b].qt_first;
+    });
+    longest = std::max(longest, l.size());
+  }
+  P.order.assign(longest * num_xcd, -1);
+  for (int x = 0; x < num_xcd; ++x)
+    for (size_t i = 0; i < lists[x].size(); ++i) P.order[i * num_xcd + x] = lists[x][i];
+  return P;
+}
+
 std::vector<std::pair<int32_t, int32_t>> uncovered_kv_ranges(const chunk_attn_desc* d) {
   std::vector<std::pair<int32_t, int32_t>> gaps;
   int32_t next = 0;

@@ -56,6 +56,39 @@ struct DkvItem {
   int32_t pad0, pad1, pad2;
 };
 
+// Work item of the one-pass backward kernel (head_dim 128): a DkvItem plus what the kernel needs to add its share of dQ
+// into the float32 dQ tiles in a fixed order.  All key blocks of one (segment, key/value head) form a chain, in
+// order of their first key; a block adds to a dQ tile after its predecessor in the chain has (every query tile a block
+// sees is also seen by its predecessor, so the first block of a chain initialises every tile).
+struct FusedItem {
+  int32_t kv_row0, kv_rows, j0, ctx, q_row_seg, q_len, qt_first, n_qt, q_tile0;  // as in DkvItem
+  int32_t kvh;        // key/value head
+  int32_t pred;       // item index of the predecessor in the chain, -1 for the chain's first block
+  int32_t delta_qt;   // qt_first - predecessor's qt_first (>= 0)
+  int32_t dq_tile0;   // index of the segment's first 32-row query tile in the dQ tile array (per head)
+  int32_t buf;        // which dQ tile array the block's sub-chain adds into
+  int32_t pad1, pad2;
+};
+// A 32-row tile of dQ for the conversion to bf16 rows.
+struct DqTileJob {
+  int32_t q_row0, valid_rows;  // first query row (global) and rows in the tile
+  int32_t tile;                // index of the tile in a dQ tile array (per head)
+  int32_t qt;                  // index of the tile inside its segment
+  int32_t ctx, n_blocks;       // context length and number of key blocks of the segment
+  int32_t pad0, pad1;
+};
+struct FusedPlan {
+  std::vector<FusedItem> items;
+  std::vector<int32_t> order;   // workgroup b runs item order[b] (-1: nothing); b % 8 is the XCD the chain is pinned to
+  std::vector<DqTileJob> tiles;
+  int64_t total_qt32 = 0;       // 32-row query tiles of all segments
+  int num_bufs = 1;
+};
+// Sub-chains per (segment, key/value head): the blocks of a chain are dealt round robin to `num_bufs` sub-chains, each
+// adding into a dQ tile array of its own (summed by the conversion), which shortens the wait along a chain.
+int fused_num_bufs(const chunk_attn_desc* d, int keys);
+FusedPlan plan_fused(const chunk_attn_desc* d, int keys, int num_xcd, int num_bufs);
+
 int validate(const chunk_attn_desc* d);
 int64_t pair_count(const chunk_attn_desc* d);
 

@@ -81,6 +81,54 @@ static int check_plan_cover(unsigned seed) {
     }
     REQUIRE(got == want);
   }
+  // the one-pass backward's plan: the same cover, and chains in which every block follows a block that sees at least
+  // the query tiles it sees, pinned to one XCD and handed out after its predecessor
+  for (int bufs : {1, 2, 4}) {
+    const chunk_attn::FusedPlan P = chunk_attn::plan_fused(&d, 128, 8, bufs);
+    std::vector<uint8_t> got((size_t)tq * tkv, 0);
+    std::vector<int> slot_of(P.items.size(), -1);
+    REQUIRE(P.order.size() % 8 == 0);
+    for (size_t b = 0; b < P.order.size(); ++b) {
+      if (P.order[b] < 0) continue;
+      REQUIRE(P.order[b] < (int)P.items.size() && slot_of[P.order[b]] < 0);
+      slot_of[P.order[b]] = (int)b;
+    }
+    int n_tiles = 0;
+    for (const auto& s : segs) n_tiles += (s.q_len + 31) / 32;
+    REQUIRE(P.total_qt32 == n_tiles && (int)P.tiles.size() == n_tiles);
+    for (size_t i = 0; i < P.items.size(); ++i) {
+      const auto& it = P.items[i];
+      REQUIRE(slot_of[i] >= 0);                                   // every item is run by exactly one workgroup
+      REQUIRE(it.kvh >= 0 && it.kvh < d.num_kv_heads && it.buf >= 0 && it.buf < bufs);
+      REQUIRE(it.kv_rows >= 1 && it.kv_rows <= 128 && it.qt_first >= 0 && it.qt_first < it.n_qt);
+      REQUIRE(it.dq_tile0 >= 0 && it.dq_tile0 + it.n_qt <= n_tiles);
+      if (it.pred >= 0) {
+        const auto& pr = P.items[it.pred];
+        REQUIRE(it.pred < (int)i && pr.kvh == it.kvh && pr.q_row_seg == it.q_row_seg && pr.buf == it.buf);
+        REQUIRE(pr.kv_row0 + 128 * bufs == it.kv_row0);             // the block `bufs` before it
+        REQUIRE(pr.qt_first <= it.qt_first && it.delta_qt == it.qt_first - pr.qt_first);
+        REQUIRE(slot_of[it.pred] % 8 == slot_of[i] % 8);            // same XCD
+        REQUIRE(slot_of[it.pred] < slot_of[i]);                     // handed out earlier
+      } else {
+        REQUIRE(it.j0 < 128 * bufs && it.delta_qt == 0);            // one of the first blocks of its segment
+      }
+      if (it.kvh != 0) continue;                                  // the pair cover, once per key/value head
+      for (int qt = it.qt_first; qt < it.n_qt; ++qt) {
+        bool any = false;
+        for (int q = 32 * qt; q < std::min(32 * qt + 32, it.q_len); ++q)
+          for (int kk = 0; kk < it.kv_rows; ++kk)
+            if (q >= it.j0 + kk - it.ctx) {
+              ++got[(size_t)(it.q_row_seg + q) * tkv + it.kv_row0 + kk];
+              any = true;
+            }
+        REQUIRE(any);
+      }
+    }
+    REQUIRE(got == want);
+    // every dQ tile is initialised: the first block of sub-chain 0 sees every tile of its segment
+    for (const auto& it : P.items)
+      if (it.pred < 0 && it.buf == 0) REQUIRE(it.qt_first == 0);
+  }
   return 0;
 }
 
