@@ -203,6 +203,27 @@ def main():
     total_flops = sum(c["fwd_flops"] + c["bwd_flops"] for c in calls)
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
+    # what the chip's clock allows under matrix load: a kernel of nothing but bf16 MFMAs, half a second of it, measured right
+    # after the timed steps (include/chunk_attn.h: chunk_attn_measure_mfma_rate)
+    measured_peak = ca.chunk_attn_measure_mfma_rate(500)
+
+    # per chunk: whole forward and whole backward calls (all their kernels), one more step with events around every call
+    call_ev = []
+    for i in fwd_order:
+        c = calls[i]
+        e0 = evpool.pair()
+        evpool.record(e0[0]); ca.chunk_attn_fwd(c["desc"], c["q"], c["k"], c["v"], c["o"], c["lse"], c["ws"]); evpool.record(e0[1])
+        call_ev.append((i, "fwd", e0))
+    for i in bwd_order:
+        c = calls[i]
+        e0 = evpool.pair()
+        evpool.record(e0[0])
+        ca.chunk_attn_bwd(c["desc"], c["q"], c["k"], c["v"], c["o"], c["do"], c["lse"], c["dq"], c["dk"], c["dv"], c["accumulate"], c["ws"])
+        evpool.record(e0[1])
+        call_ev.append((i, "bwd", e0))
+    torch.cuda.synchronize()
+    call_ms = {(i, kind): evpool.elapsed_ms(*ev) for i, kind, ev in call_ev}
+
     # per-kernel durations from the HIP events recorded on the launch stream
     per_call = []
     fwd_k_ms = bwd_k_ms = 0.0
@@ -210,10 +231,14 @@ def main():
         f = sum(evpool.elapsed_ms(*e) for e in c["fwd_ms"]) / args.steps
         b = sum(evpool.elapsed_ms(*e) for e in c["bwd_ms"]) / args.steps
         fwd_k_ms += f; bwd_k_ms += b
+        ci = calls.index(c)
+        fw, bw = call_ms[(ci, "fwd")], call_ms[(ci, "bwd")]
         per_call.append({"call": c["name"], "pairs_per_head": c["pairs"], "fwd_kernel_ms": round(f, 4),
                          "bwd_dkv_kernel_ms": round(b, 4),
                          "fwd_tflops": round(c["fwd_flops"] / f / 1e9, 1),
-                         "bwd_dkv_kernel_tflops": round(0.8 * c["bwd_flops"] / b / 1e9, 1)})
+                         "bwd_dkv_kernel_tflops": round(0.8 * c["bwd_flops"] / b / 1e9, 1),
+                         "fwd_call_ms": round(fw, 4), "bwd_call_ms": round(bw, 4),
+                         "fwd_bwd_tflops": round((c["fwd_flops"] + c["bwd_flops"]) / (fw + bw) / 1e9, 1)})
     evpool.close()
     bwd_flops = sum(c["bwd_flops"] for c in calls)
     fwd_flops = sum(c["fwd_flops"] for c in calls)
@@ -222,6 +247,18 @@ def main():
     # (query, key) pair and query head -- S, dP, dV, dK -- i.e. 8 * head_dim flops, 0.8 of the backward's 10 * head_dim.
     dkv_flops = 0.8 * bwd_flops
     achieved = dkv_flops / (bwd_k_ms * 1e-3) / 1e12
+
+    # the two workloads the target names, each by itself (whole calls, all kernels)
+    def shape_row(names):
+        sel = [c for c in calls if c["name"] in names or any(c["name"].startswith(n) for n in names)]
+        if not sel:
+            return None
+        fl = sum(c["fwd_flops"] + c["bwd_flops"] for c in sel)
+        ms = sum(call_ms[(calls.index(c), "fwd")] + call_ms[(calls.index(c), "bwd")] for c in sel)
+        tf = fl / ms / 1e9
+        return {"tflops": round(tf, 1), "ms": round(ms, 3), "pct_of_bf16_mfma_peak": round(100.0 * tf / PEAK_BF16_TFLOPS, 2),
+                "pct_of_measured_clock_peak": round(100.0 * tf / measured_peak, 2)}
+    per_shape = {"packed_64k": shape_row(["packed_64k"]), "split_128k_x8": shape_row(["split_128k_slice"])}
 
     out = {
         "metric": "chunk attention fwd+bwd causal TFLOP/s, 1 MI355X",
@@ -235,8 +272,13 @@ def main():
                    "calls_per_step": 2 * n_launch, "flops_per_step": total_flops,
                    "seed_base": synth.BASE_SEED},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "target": {"pct_of_bf16_mfma_peak": 50.0, "met": bool(value >= 0.5 * PEAK_BF16_TFLOPS)},
+        "pct_of_measured_clock_peak": round(100.0 * value / measured_peak, 2),
+        "per_shape": per_shape,
         "roofline": {"kernel": "bwd_dkv_pipe_kernel<128>", "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "measured_clock_peak": round(measured_peak, 1),
+                     "frac_of_measured_clock_peak": round(achieved / measured_peak, 4),
                      "traffic": recorded_traffic(), "launches_per_step": n_launch,
                      "avg_launch_ms": round(bwd_k_ms / n_launch, 4),
                      "flops_per_launch_avg": dkv_flops / n_launch,

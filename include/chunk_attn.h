@@ -184,6 +184,16 @@ int chunk_attn_shutdown(void);
 int chunk_attn_test_set_fwd_rescale_limit(float log2_growth);
 
 /*
+ * Measurement hook (not part of the method): the bf16 matrix throughput this GPU sustains when a kernel issues nothing
+ * but independent v_mfma_f32_32x32x16_bf16 instructions on random operands, one workgroup of four waves per CU, for
+ * about `milliseconds` (1 .. 10000) of GPU time; the rate of the last launch goes to *tflops.  Under sustained matrix
+ * load the chip runs below its 2.4 GHz peak clock, so this -- not the published 2516.6 TFLOP/s -- is the ceiling any
+ * kernel sees.  `scratch`: DEVICE memory, 256-byte aligned, at least 1052672 bytes (else
+ * CHUNK_ATTN_WORKSPACE_TOO_SMALL).  Synchronises `stream`.
+ */
+int chunk_attn_measure_mfma_rate(int milliseconds, void* scratch, size_t scratch_bytes, void* stream, double* tflops);
+
+/*
  * Test and measurement hook: which backward chunk_attn_bwd / chunk_attn_bwd_f32kv run for head_dim 128.
  * 0: the library's choice; 1: two kernels (dQ query-stationary, dK/dV key-stationary, P recomputed in both);
  * 2: one pass (the key-stationary kernel also forms dQ and adds it into float32 tiles in the workspace in a fixed

@@ -203,6 +203,18 @@ def chunk_attn_test_set_fwd_rescale_limit(log2_growth: float) -> None:
     _lib.chunk_attn_test_set_fwd_rescale_limit(ctypes.c_float(log2_growth))
 
 
+def chunk_attn_measure_mfma_rate(milliseconds: int = 500, stream=None) -> float:
+    """Measurement hook: TFLOP/s this GPU sustains on bf16 matrix instructions alone (its clock under matrix load)."""
+    import torch
+    scratch = torch.empty(1052672, dtype=torch.uint8, device="cuda")
+    out = ctypes.c_double(0.0)
+    rc = _lib.chunk_attn_measure_mfma_rate(ctypes.c_int(milliseconds), _ptr(scratch), ctypes.c_size_t(scratch.numel()),
+                                           _stream(stream), ctypes.byref(out))
+    if rc != 0:
+        raise ChunkAttnError(rc)
+    return out.value
+
+
 def chunk_attn_test_set_bwd_mode(mode: int) -> None:
     """Test hook: 0 = library's choice, 1 = two-kernel backward, 2 = one-pass backward (head_dim 128)."""
     rc = _lib.chunk_attn_test_set_bwd_mode(ctypes.c_int(mode))
@@ -234,7 +246,14 @@ class HipEvents:
         self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self._hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         self._all = []
+
+    def record(self, event, stream=None) -> None:
+        """Records `event` on `stream` (default: torch's current stream)."""
+        rc = self._hip.hipEventRecord(ctypes.c_void_p(event), _stream(stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
 
     def pair(self):
         evs = []

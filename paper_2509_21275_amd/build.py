@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libchunk_attn.so")
-SOURCES = ["plan.cpp", "chunk_plan.cpp", "chunk_sched.cpp", "fused_ce.hip", "transpose_kernel.hip", "fwd_kernel.hip", "bwd_kernel.hip", "bwd_fused_kernel.hip", "api.hip"]
+SOURCES = ["plan.cpp", "chunk_plan.cpp", "chunk_sched.cpp", "fused_ce.hip", "transpose_kernel.hip", "fwd_kernel.hip", "bwd_kernel.hip", "bwd_fused_kernel.hip", "measure.hip", "api.hip"]
 # -packed-fp32-ops off: the compiler must not form packed fp32 VALU instructions on this target
 # -fno-honor-nans: no input of these kernels is NaN; it lets max/compare lower to single instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-fno-honor-nans",
