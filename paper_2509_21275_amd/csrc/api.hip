@@ -288,7 +288,7 @@ const char* chunk_attn_strerror(int code) {
   switch (code) {
     case CHUNK_ATTN_OK: return "ok";
     case CHUNK_ATTN_INVALID_ARG: return "invalid argument (null pointer, non-positive size or bad scale)";
-    case CHUNK_ATTN_UNSUPPORTED: return "unsupported shape (head_dim must be 64 or 128; num_kv_heads must divide num_q_heads)";
+    case CHUNK_ATTN_UNSUPPORTED: return "unsupported shape (head_dim must be 64, 128 or 256; num_kv_heads must divide num_q_heads)";
     case CHUNK_ATTN_BAD_SEGMENT: return "bad segment table";
     case CHUNK_ATTN_WORKSPACE_TOO_SMALL: return "workspace too small (see chunk_attn_workspace_bytes)";
     case CHUNK_ATTN_TOO_LARGE:

@@ -89,7 +89,7 @@ struct DqParams {
 };
 
 template <int D, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void bwd_dq_kernel(DqParams p) {
+__global__ __launch_bounds__(WAVES * 64, D > 128 ? 1 : 8 / WAVES) void bwd_dq_kernel(DqParams p) {
   constexpr int NTH = WAVES * 64;  // threads
   constexpr int BN = 32;       // key rows per LDS tile
   constexpr int KC = D / 8;    // 16-byte chunks per K / V row
@@ -346,7 +346,7 @@ __device__ __forceinline__ void dkv_store4(const DkvParams& p, __bf16* out, int6
 
 
 template <int D, int KB>  // KB: 32-key blocks per workgroup (2 KB waves)
-__global__ __launch_bounds__(KB * 128, 4 / KB) void bwd_dkv_kernel(DkvParams p) {
+__global__ __launch_bounds__(KB * 128, D > 128 ? 1 : 4 / KB) void bwd_dkv_kernel(DkvParams p) {
   constexpr int NW = 2 * KB;   // waves
   constexpr int NTH = NW * 64; // threads
   constexpr int BM = 32;       // query rows per step
@@ -1510,7 +1510,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
     p.out_f32 = a.dkv_f32 ? 1 : 0;
-    static_assert(DKV_KEYS == 128, "both kernels cover 128 keys per workgroup");
+    static_assert(DKV_KEYS == 128, "the head_dim 64 and 128 kernels cover 128 keys per workgroup");
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     ProfileEvents pe = profile_events();
@@ -1525,7 +1525,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
       hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
     } else {
       // 4 ring slots of two 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
-      constexpr int KB = DKV_KEYS / 32;
+      constexpr int KB = (D > 128 ? 64 : DKV_KEYS) / 32;   // as dkv_keys(D)
       const size_t smem = (size_t)8 * 32 * D * 2 + 2 * KB * 1024 * 2 + 2 * 4 * 64 * sizeof(float);
       static const hipError_t attr = raise_smem_limit(&bwd_dkv_kernel<D, KB>, smem);
       if (attr != hipSuccess) return attr;
@@ -1602,7 +1602,8 @@ std::vector<char> bwd_blob(const BwdPlan& P) {
 }
 
 hipError_t launch_bwd(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& P, hipStream_t stream) {
-  return d->head_dim == 128 ? launch_bwd_t<128>(d, a, P, stream) : launch_bwd_t<64>(d, a, P, stream);
+  return d->head_dim == 128 ? launch_bwd_t<128>(d, a, P, stream)
+         : d->head_dim == 256 ? launch_bwd_t<256>(d, a, P, stream) : launch_bwd_t<64>(d, a, P, stream);
 }
 
 }  // namespace chunk_attn

@@ -29,7 +29,7 @@
 namespace chunk_attn {
 
 template <int D, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void fwd_kernel(FwdParams p) {
+__global__ __launch_bounds__(WAVES * 64, D > 128 ? 1 : 8 / WAVES) void fwd_kernel(FwdParams p) {
   constexpr int QB = 1;        // 32-row query blocks per wave
   constexpr int NT = WAVES * 64;  // threads
   constexpr int BN = 64;       // key rows per LDS tile
@@ -633,7 +633,7 @@ hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, const Ti
   if (head_dim != 128) {
     if ((e = launch_transpose(p.v, p.num_kv_heads, head_dim, 64, vjobs, num_vjobs, p.total_kv_tiles, const_cast<__bf16*>(p.vt),
                               stream)) != hipSuccess) return e;
-    return launch_fwd_t<64, 4>(p, num_blocks, stream);
+    return head_dim == 256 ? launch_fwd_t<256, 4>(p, num_blocks, stream) : launch_fwd_t<64, 4>(p, num_blocks, stream);
   }
   const size_t smem = (size_t)2 * (FWD_PIPE_DIST + 3) * 32 * 128 * 2;  // ring slots of a K and a V tile
   static const hipError_t attr = raise_smem_limit(&fwd_pipe_kernel<128>, smem);

@@ -43,8 +43,8 @@ inline int heads_per_wg(int group, int waves) {
   while (h * 2 <= waves && group % (h * 2) == 0) h *= 2;
   return h;
 }
-// key rows per work item of the dK/dV kernel (32 per pair of waves)
-inline int dkv_keys(int) { return DKV_KEYS; }
+// key rows per work item of the dK/dV kernel (32 per pair of waves); head_dim 256 leaves room for two pairs only
+inline int dkv_keys(int head_dim) { return head_dim > 128 ? 64 : DKV_KEYS; }
 inline int tile_rows(int group, int waves) { return 32 * (waves / heads_per_wg(group, waves)); }
 
 // Events armed by chunk_attn_profile_events for the calling thread (null when disarmed).

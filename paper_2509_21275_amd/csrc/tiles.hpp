@@ -16,7 +16,11 @@ namespace chunk_attn {
 // physical chunk position of logical chunk c in row `row` of a tile with CHUNKS 16-byte chunks per row
 template <int CHUNKS>
 __device__ __forceinline__ int swz(int row, int c) {
-  if constexpr (CHUNKS == 16) {
+  if constexpr (CHUNKS == 32) {
+    // 512-byte rows: every row starts on the same bank, so the chunk is rotated by the row index; 16 consecutive rows then
+    // fall on 16 distinct bank groups
+    return (c + row) & 31;
+  } else if constexpr (CHUNKS == 16) {
     // 256-byte rows: rotate by a 4x4 bit-transposed row index; conflict-free for 16 consecutive rows
     const int f = ((row & 3) << 2) | ((row >> 2) & 3);
     return (c + f) & 15;
@@ -24,7 +28,7 @@ __device__ __forceinline__ int swz(int row, int c) {
     // 128-byte rows: two rows share a 256-byte bank line, so the permutation changes every other row
     return c ^ ((row >> 1) & 7);
   } else {
-    static_assert(CHUNKS == 4, "tiles have 4, 8 or 16 chunks per row");
+    static_assert(CHUNKS == 4, "tiles have 4, 8, 16 or 32 chunks per row");
     // 64-byte rows: four rows share a bank line
     return c ^ ((row >> 2) & 3);
   }
@@ -32,7 +36,9 @@ __device__ __forceinline__ int swz(int row, int c) {
 // logical chunk stored at physical position pc (inverse of swz)
 template <int CHUNKS>
 __device__ __forceinline__ int unswz(int row, int pc) {
-  if constexpr (CHUNKS == 16) {
+  if constexpr (CHUNKS == 32) {
+    return (pc - row) & 31;
+  } else if constexpr (CHUNKS == 16) {
     const int f = ((row & 3) << 2) | ((row >> 2) & 3);
     return (pc - f) & 15;
   } else if constexpr (CHUNKS == 8) {

@@ -60,6 +60,8 @@ hipError_t launch_transpose(const __bf16* x, int num_heads, int head_dim, int wi
   else if (head_dim == 128 && width == 32) launch_t<128, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
   else if (head_dim == 64 && width == 64) launch_t<64, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
   else if (head_dim == 64 && width == 32) launch_t<64, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
+  else if (head_dim == 256 && width == 64) launch_t<256, 64>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
+  else if (head_dim == 256 && width == 32) launch_t<256, 32>(x, num_heads, jobs, blocks, total_tiles, out, stream, gate);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

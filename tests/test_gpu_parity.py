@@ -53,6 +53,12 @@ EDGE = [
     ("d128_tiny_walks", [(0, 32, 0, 32), (32, 33, 32, 33), (65, 64, 65, 64), (129, 1, 129, 129), (130, 95, 258, 95)], 2, 2, 128),
     # several segments with a context each, key ranges of 127 / 128 / 129 rows around a workgroup's 128 keys
     ("d128_many_contexts", [(0, 40, 0, 127), (40, 40, 127, 128), (80, 40, 255, 129), (120, 200, 384, 513)], 8, 2, 128),
+    # head_dim 256 (a variant of the path: other head dimensions)
+    ("d256_one_token", [(0, 1, 0, 1)], 2, 2, 256),
+    ("d256_ragged_tail_slice", [(0, 130, 0, 1000)], 8, 2, 256),
+    ("d256_hybrid_with_gaps", [(0, 150, 5, 400), (150, 70, 420, 70), (220, 1, 500, 1), (221, 300, 512, 300)], 8, 2, 256),
+    ("d256_mha_packed", [(0, 300, 0, 300), (300, 260, 300, 260), (560, 33, 560, 33)], 3, 3, 256),
+    ("d256_many_contexts", [(0, 40, 0, 63), (40, 40, 63, 64), (80, 40, 127, 65), (120, 200, 192, 513)], 8, 1, 256),
 ]
 
 
