@@ -54,7 +54,7 @@ extern "C" {
 enum {
   CHUNK_ATTN_OK = 0,
   CHUNK_ATTN_INVALID_ARG = -1,         /* null pointer, non-positive dimension, bad scale */
-  CHUNK_ATTN_UNSUPPORTED = -2,         /* head_dim not 64, 128 or 256, or num_q_heads % num_kv_heads != 0 */
+  CHUNK_ATTN_UNSUPPORTED = -2,         /* head_dim not 64, 96, 128 or 256, or num_q_heads % num_kv_heads != 0 */
   CHUNK_ATTN_BAD_SEGMENT = -3,         /* see chunk_attn_desc.segments */
   CHUNK_ATTN_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes below chunk_attn_workspace_bytes */
   CHUNK_ATTN_HIP_ERROR = -5,           /* a HIP call or kernel launch failed */
@@ -69,7 +69,7 @@ typedef struct {
 typedef struct {
   int32_t num_q_heads;  /* Hq > 0 */
   int32_t num_kv_heads; /* Hkv > 0, divides Hq */
-  int32_t head_dim;     /* 64, 128 or 256 */
+  int32_t head_dim;     /* 64, 96, 128 or 256 (96 runs as 128 on zero-padded copies in the workspace) */
   int32_t total_q;      /* rows of q / o / d_o / dq */
   int32_t total_kv;     /* rows of k / v / dk / dv */
   int32_t num_segments; /* >= 1 */

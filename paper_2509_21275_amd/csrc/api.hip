@@ -2,6 +2,7 @@
 // schedule upload and kernel launches.  No device memory is allocated here; the only memory the
 // library owns is a small ring of pinned host buffers through which tile schedules are uploaded
 // (released by chunk_attn_shutdown).
+#include <algorithm>
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
@@ -232,6 +233,94 @@ __global__ __launch_bounds__(256) void plan_fwd_static_kernel(StaticSegs segs, i
   for (int x = threadIdx.x; x < n_flags; x += 256) flags[x] = 0;
 }
 
+// ---- head_dim 96 ----
+// The kernels tile the head dimension in powers of two.  A head of 96 is run as a head of 128 whose last 32 columns
+// are zero: zero columns of Q and K add nothing to a score, zero columns of V and dO give zero columns of O, dV and (through
+// dS K, dS^T Q) of dQ and dK, and D_i = <dO_i, O_i> is unchanged, so every result is the 96-wide one exactly, with the
+// softmax scale the caller gave.  The padded copies live at the head of the workspace; rows move in 16-byte chunks.
+constexpr int kNarrowDim = 96, kPaddedDim = 128;
+
+inline bool is_narrow(const chunk_attn_desc* d) { return d->head_dim == kNarrowDim; }
+inline chunk_attn_desc widened(const chunk_attn_desc* d) {
+  chunk_attn_desc w = *d;
+  w.head_dim = kPaddedDim;
+  return w;
+}
+inline size_t padded_bytes(int64_t rows, int heads, size_t elem) { return align_up((size_t)rows * heads * kPaddedDim * elem); }
+
+// dst[row][0 .. out_chunks) = src[row][0 .. in_chunks) followed by zero chunks
+__global__ __launch_bounds__(256) void pad_rows_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n_out,
+                                                       int in_chunks, int out_chunks) {
+  for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_out; x += (int64_t)gridDim.x * 256) {
+    const int64_t row = x / out_chunks;
+    const int c = (int)(x - row * out_chunks);
+    dst[x] = c < in_chunks ? src[row * in_chunks + c] : make_uint4(0, 0, 0, 0);
+  }
+}
+// dst[row][0 .. in_chunks) = src[row][0 .. in_chunks) of rows that are out_chunks wide
+__global__ __launch_bounds__(256) void unpad_rows_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n_in,
+                                                         int in_chunks, int out_chunks) {
+  for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_in; x += (int64_t)gridDim.x * 256) {
+    const int64_t row = x / in_chunks;
+    const int c = (int)(x - row * in_chunks);
+    dst[x] = src[row * out_chunks + c];
+  }
+}
+inline int copy_grid(int64_t n) { return (int)std::min<int64_t>((n + 255) / 256, 256 * 16); }
+// rows = tensor rows * heads; elem = bytes per element
+hipError_t pad_rows(const void* src, void* dst, int64_t rows, size_t elem, hipStream_t stream) {
+  const int in_chunks = kNarrowDim * (int)elem / 16, out_chunks = kPaddedDim * (int)elem / 16;
+  const int64_t n = rows * out_chunks;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(pad_rows_kernel, dim3(copy_grid(n)), dim3(256), 0, stream, static_cast<const uint4*>(src),
+                     static_cast<uint4*>(dst), n, in_chunks, out_chunks);
+  return hipGetLastError();
+}
+hipError_t unpad_rows(const void* src, void* dst, int64_t rows, size_t elem, hipStream_t stream) {
+  const int in_chunks = kNarrowDim * (int)elem / 16, out_chunks = kPaddedDim * (int)elem / 16;
+  const int64_t n = rows * in_chunks;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(unpad_rows_kernel, dim3(copy_grid(n)), dim3(256), 0, stream, static_cast<const uint4*>(src),
+                     static_cast<uint4*>(dst), n, in_chunks, out_chunks);
+  return hipGetLastError();
+}
+
+// Padded copies at the head of a workspace, the widened call's own workspace behind them.
+struct NarrowFwdLayout {
+  size_t q_off, k_off, v_off, o_off, inner_off, total;
+};
+NarrowFwdLayout narrow_fwd_layout(const chunk_attn_desc* d, size_t inner_bytes) {
+  const size_t qb = padded_bytes(d->total_q, d->num_q_heads, 2), kb = padded_bytes(d->total_kv, d->num_kv_heads, 2);
+  NarrowFwdLayout N;
+  N.q_off = 0;
+  N.k_off = qb;
+  N.v_off = N.k_off + kb;
+  N.o_off = N.v_off + kb;
+  N.inner_off = N.o_off + qb;
+  N.total = N.inner_off + inner_bytes;
+  return N;
+}
+struct NarrowBwdLayout {
+  size_t q_off, k_off, v_off, o_off, do_off, dq_off, dk_off, dv_off, inner_off, total;
+};
+// dk / dv copies are sized for float32, whichever entry point is called later
+NarrowBwdLayout narrow_bwd_layout(const chunk_attn_desc* d, size_t inner_bytes) {
+  const size_t qb = padded_bytes(d->total_q, d->num_q_heads, 2), kb = padded_bytes(d->total_kv, d->num_kv_heads, 2);
+  const size_t gb = padded_bytes(d->total_kv, d->num_kv_heads, 4);
+  NarrowBwdLayout N;
+  N.q_off = 0;
+  N.k_off = qb;
+  N.v_off = N.k_off + kb;
+  N.o_off = N.v_off + kb;
+  N.do_off = N.o_off + qb;
+  N.dq_off = N.do_off + qb;
+  N.dk_off = N.dq_off + qb;
+  N.dv_off = N.dk_off + gb;
+  N.inner_off = N.dv_off + gb;
+  N.total = N.inner_off + inner_bytes;
+  return N;
+}
+
 }  // namespace
 
 namespace chunk_attn {
@@ -267,9 +356,11 @@ int chunk_attn_test_bwd_status_offset(const chunk_attn_desc* desc, size_t* offse
   const int rc = validate(desc);
   if (rc != CHUNK_ATTN_OK) return rc;
   if (!offset) return CHUNK_ATTN_INVALID_ARG;
+  const chunk_attn_desc w = is_narrow(desc) ? widened(desc) : *desc;
   BwdPlan P;
-  bwd_layout(desc, P, false);
+  bwd_layout(&w, P, false);
   *offset = P.fprog_off + P.fprog_bytes - kFusedSinkBytes - 256;
+  if (is_narrow(desc)) *offset += narrow_bwd_layout(desc, P.total).inner_off;
   return CHUNK_ATTN_OK;
 }
 
@@ -288,7 +379,7 @@ const char* chunk_attn_strerror(int code) {
   switch (code) {
     case CHUNK_ATTN_OK: return "ok";
     case CHUNK_ATTN_INVALID_ARG: return "invalid argument (null pointer, non-positive size or bad scale)";
-    case CHUNK_ATTN_UNSUPPORTED: return "unsupported shape (head_dim must be 64, 128 or 256; num_kv_heads must divide num_q_heads)";
+    case CHUNK_ATTN_UNSUPPORTED: return "unsupported shape (head_dim must be 64, 96, 128 or 256; num_kv_heads must divide num_q_heads)";
     case CHUNK_ATTN_BAD_SEGMENT: return "bad segment table";
     case CHUNK_ATTN_WORKSPACE_TOO_SMALL: return "workspace too small (see chunk_attn_workspace_bytes)";
     case CHUNK_ATTN_TOO_LARGE:
@@ -306,15 +397,16 @@ const char* chunk_attn_strerror(int code) {
 int chunk_attn_workspace_bytes(const chunk_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes) {
   const int rc = validate(desc);
   if (rc != CHUNK_ATTN_OK) return rc;
+  const chunk_attn_desc w = is_narrow(desc) ? widened(desc) : *desc;
   if (fwd_bytes) {
     FwdLayout L;
-    layout_fwd(desc, L, false);
-    *fwd_bytes = L.total;
+    layout_fwd(&w, L, false);
+    *fwd_bytes = is_narrow(desc) ? narrow_fwd_layout(desc, L.total).total : L.total;
   }
   if (bwd_bytes) {
     BwdPlan P;
-    bwd_layout(desc, P, false);
-    *bwd_bytes = P.total;
+    bwd_layout(&w, P, false);
+    *bwd_bytes = is_narrow(desc) ? narrow_bwd_layout(desc, P.total).total : P.total;
   }
   return CHUNK_ATTN_OK;
 }
@@ -327,6 +419,25 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0) return CHUNK_ATTN_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(lse) & 3) != 0)
     return CHUNK_ATTN_INVALID_ARG;  // the kernels move rows in 16-byte pieces
+  if (is_narrow(desc)) {  // run as head_dim 128 on zero-padded copies
+    const chunk_attn_desc w = widened(desc);
+    FwdLayout Lw;
+    layout_fwd(&w, Lw, false);
+    const NarrowFwdLayout N = narrow_fwd_layout(desc, Lw.total);
+    if (workspace_bytes < N.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    const int64_t qr = (int64_t)desc->total_q * desc->num_q_heads, kr = (int64_t)desc->total_kv * desc->num_kv_heads;
+    hipError_t pe;
+    if ((pe = pad_rows(q, base + N.q_off, qr, 2, st)) != hipSuccess || (pe = pad_rows(k, base + N.k_off, kr, 2, st)) != hipSuccess ||
+        (pe = pad_rows(v, base + N.v_off, kr, 2, st)) != hipSuccess)
+      return hip_fail(pe, "padding launch");
+    const int r = chunk_attn_fwd(&w, base + N.q_off, base + N.k_off, base + N.v_off, base + N.o_off, lse, base + N.inner_off,
+                                 workspace_bytes - N.inner_off, stream_v);
+    if (r != CHUNK_ATTN_OK) return r;
+    if ((pe = unpad_rows(base + N.o_off, o, qr, 2, st)) != hipSuccess) return hip_fail(pe, "unpadding launch");
+    return CHUNK_ATTN_OK;
+  }
   FwdLayout L;
   layout_fwd(desc, L, true);
   if (workspace_bytes < L.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
@@ -377,14 +488,29 @@ int chunk_attn_fwd_static(const chunk_attn_desc* desc, const void* q, const void
   if (!q || !k || !v || !o || !lse) return CHUNK_ATTN_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(lse) & 3) != 0)
     return CHUNK_ATTN_INVALID_ARG;
+  const chunk_attn_desc wide = is_narrow(desc) ? widened(desc) : *desc;
   FwdLayout L;
-  layout_fwd(desc, L, false);
-  if (desc->num_segments > kStaticMaxSegments || L.total > kStaticScratchBytes || L.blocks > 0x7fffffff)
+  layout_fwd(&wide, L, false);
+  const NarrowFwdLayout N = is_narrow(desc) ? narrow_fwd_layout(desc, L.total) : NarrowFwdLayout{0, 0, 0, 0, 0, L.total};
+  if (desc->num_segments > kStaticMaxSegments || N.total > kStaticScratchBytes || L.blocks > 0x7fffffff)
     return CHUNK_ATTN_TOO_LARGE;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   char* ws = nullptr;
   hipError_t e = static_scratch(&ws);
   if (e != hipSuccess) return hip_fail(e, "address of the static scratch buffer");
+  void* o_user = o;
+  const int64_t qr = (int64_t)desc->total_q * desc->num_q_heads, kr = (int64_t)desc->total_kv * desc->num_kv_heads;
+  if (is_narrow(desc)) {  // zero-padded copies at the head of the scratch array, the head_dim 128 forward behind them
+    if ((e = pad_rows(q, ws + N.q_off, qr, 2, stream)) != hipSuccess || (e = pad_rows(k, ws + N.k_off, kr, 2, stream)) != hipSuccess ||
+        (e = pad_rows(v, ws + N.v_off, kr, 2, stream)) != hipSuccess)
+      return hip_fail(e, "padding launch");
+    q = ws + N.q_off;
+    k = ws + N.k_off;
+    v = ws + N.v_off;
+    o = ws + N.o_off;
+    ws += N.inner_off;
+    desc = &wide;
+  }
 
   StaticSegs segs;
   for (int t = 0; t < desc->num_segments; ++t) segs.seg[t] = desc->segments[t];
@@ -415,6 +541,7 @@ int chunk_attn_fwd_static(const chunk_attn_desc* desc, const void* q, const void
   p.ref_limit = g_fwd_rescale_limit.load();
   e = launch_fwd(p, desc->head_dim, (int)L.blocks, reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.kv_tiles, stream);
   if (e != hipSuccess) return hip_fail(e, "forward launch");
+  if (o != o_user && (e = unpad_rows(o, o_user, qr, 2, stream)) != hipSuccess) return hip_fail(e, "unpadding launch");
   return CHUNK_ATTN_OK;
 }
 
@@ -429,6 +556,34 @@ int bwd_any(const chunk_attn_desc* desc, const void* q, const void* k, const voi
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) ||
       !aligned16(dv) || (reinterpret_cast<uintptr_t>(lse) & 3) != 0)
     return CHUNK_ATTN_INVALID_ARG;  // the kernels move rows in 16-byte pieces
+  if (is_narrow(desc)) {  // run as head_dim 128 on zero-padded copies
+    const chunk_attn_desc w = widened(desc);
+    BwdPlan Pw;
+    bwd_layout(&w, Pw, false);
+    const NarrowBwdLayout N = narrow_bwd_layout(desc, Pw.total);
+    if (workspace_bytes < N.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    const int64_t qr = (int64_t)desc->total_q * desc->num_q_heads, kr = (int64_t)desc->total_kv * desc->num_kv_heads;
+    const size_t ge = dkv_f32 ? 4 : 2;
+    hipError_t pe;
+    if ((pe = pad_rows(q, base + N.q_off, qr, 2, st)) != hipSuccess || (pe = pad_rows(k, base + N.k_off, kr, 2, st)) != hipSuccess ||
+        (pe = pad_rows(v, base + N.v_off, kr, 2, st)) != hipSuccess || (pe = pad_rows(o, base + N.o_off, qr, 2, st)) != hipSuccess ||
+        (pe = pad_rows(d_o, base + N.do_off, qr, 2, st)) != hipSuccess)
+      return hip_fail(pe, "padding launch");
+    // accumulating calls add to what dk / dv hold and leave the rows outside every key range as they are
+    if (accumulate_dkv && ((pe = pad_rows(dk, base + N.dk_off, kr, ge, st)) != hipSuccess ||
+                           (pe = pad_rows(dv, base + N.dv_off, kr, ge, st)) != hipSuccess))
+      return hip_fail(pe, "padding launch");
+    const int r = bwd_any(&w, base + N.q_off, base + N.k_off, base + N.v_off, base + N.o_off, base + N.do_off, lse,
+                          base + N.dq_off, base + N.dk_off, base + N.dv_off, dkv_f32, accumulate_dkv, base + N.inner_off,
+                          workspace_bytes - N.inner_off, stream_v);
+    if (r != CHUNK_ATTN_OK) return r;
+    if ((pe = unpad_rows(base + N.dq_off, dq, qr, 2, st)) != hipSuccess || (pe = unpad_rows(base + N.dk_off, dk, kr, ge, st)) != hipSuccess ||
+        (pe = unpad_rows(base + N.dv_off, dv, kr, ge, st)) != hipSuccess)
+      return hip_fail(pe, "unpadding launch");
+    return CHUNK_ATTN_OK;
+  }
   BwdPlan P;
   bwd_layout(desc, P, true);
   if (workspace_bytes < P.total) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;

@@ -11,7 +11,7 @@ int validate(const chunk_attn_desc* d) {
       d->num_segments <= 0)
     return CHUNK_ATTN_INVALID_ARG;
   if (!(d->softmax_scale > 0.0f) || !std::isfinite(d->softmax_scale)) return CHUNK_ATTN_INVALID_ARG;
-  if (d->head_dim != 64 && d->head_dim != 128 && d->head_dim != 256) return CHUNK_ATTN_UNSUPPORTED;
+  if (d->head_dim != 64 && d->head_dim != 96 && d->head_dim != 128 && d->head_dim != 256) return CHUNK_ATTN_UNSUPPORTED;
   if (d->num_q_heads % d->num_kv_heads != 0) return CHUNK_ATTN_UNSUPPORTED;
   int64_t q_next = 0, kv_next = 0;
   for (int t = 0; t < d->num_segments; ++t) {

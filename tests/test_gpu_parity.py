@@ -59,6 +59,11 @@ EDGE = [
     ("d256_hybrid_with_gaps", [(0, 150, 5, 400), (150, 70, 420, 70), (220, 1, 500, 1), (221, 300, 512, 300)], 8, 2, 256),
     ("d256_mha_packed", [(0, 300, 0, 300), (300, 260, 300, 260), (560, 33, 560, 33)], 3, 3, 256),
     ("d256_many_contexts", [(0, 40, 0, 63), (40, 40, 63, 64), (80, 40, 127, 65), (120, 200, 192, 513)], 8, 1, 256),
+    # head_dim 96
+    ("d96_one_token", [(0, 1, 0, 1)], 2, 2, 96),
+    ("d96_ragged_tail_slice", [(0, 130, 0, 1000)], 8, 2, 96),
+    ("d96_hybrid_with_gaps", [(0, 150, 5, 400), (150, 70, 420, 70), (220, 1, 500, 1), (221, 300, 512, 300)], 8, 2, 96),
+    ("d96_mha_packed", [(0, 300, 0, 300), (300, 260, 300, 260), (560, 33, 560, 33)], 3, 3, 96),
 ]
 
 

@@ -63,7 +63,7 @@ def test_valid_descriptors(ca):
     ([(0, 4, 0, 4), (4, 4, 2, 4)], {}, "BAD_SEGMENT"),            # overlapping key ranges
     ([(0, 4, 0, 4)], {"tq": 6}, "BAD_SEGMENT"),                   # queries do not cover total_q
     ([(0, 4, 0, 8)], {"tkv": 6}, "BAD_SEGMENT"),                  # key range past total_kv
-    ([(0, 4, 0, 4)], {"d": 96}, "UNSUPPORTED"),
+    ([(0, 4, 0, 4)], {"d": 80}, "UNSUPPORTED"),
     ([(0, 4, 0, 4)], {"Hq": 6, "Hkv": 4}, "UNSUPPORTED"),
     ([(0, 4, 0, 4)], {"scale": 0.0}, "INVALID_ARG"),
     ([(0, 4, 0, 4)], {"scale": float("nan")}, "INVALID_ARG"),

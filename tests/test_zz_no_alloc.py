@@ -1,6 +1,6 @@
 """chunk_attn_fwd_static, the forward that allocates nothing (its scratch memory is a fixed array inside the library),
 against chunk_attn_fwd on the same inputs: identical bits, on two calls in a row, the second on a smaller chunk (the
-array keeps the first call's contents), for both head dimensions; chunks beyond its limits are refused on the host."""
+array keeps the first call's contents), for every head dimension; chunks beyond its limits are refused on the host."""
 import ctypes
 
 import pytest
@@ -31,7 +31,7 @@ def _both(ca, lib, case):
     assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
 
 
-@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("d", [128, 64, 96, 256])
 def test_static_forward_matches_the_workspace_forward_twice(d):
     import paper_2509_21275_amd as ca
     lib = ctypes.CDLL(ca.LIB_PATH)
