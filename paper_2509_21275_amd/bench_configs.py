@@ -1,13 +1,16 @@
 """Forward and backward throughput of the five workload shapes, one after the other, on one GPU.
 
-    python -m paper_2509_21275_amd.bench_configs [--markdown out.md]
+    python -m paper_2509_21275_amd.bench_configs [--markdown out.md] [--variants]
 
 Inputs resident in HBM, median of 5 timed calls after 2 warm-up calls, causal flops (4 d per unmasked pair and query head
 forward, 10 d backward).  The split sequence (shape 5) is reported for its first, middle and last slice.
+--variants adds the packed 64K chunk and the middle slice of the split sequence at head dimensions 64, 96 and 256 (same
+head counts) and with the one-pass backward of head dimension 128.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 
 import numpy as np
 import torch
@@ -46,19 +49,32 @@ def measure(case):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--markdown", default=None)
+    ap.add_argument("--variants", action="store_true")
     args = ap.parse_args()
     cases = [synth.case_by_index(i) for i in (1, 2, 3, 4)] + [synth.case_by_index(5, s) for s in (0, 3, 7)]
     # bring the chip to its sustained clock before anything is timed
     measure(cases[1])
     lines = ["| shape | heads (q/kv), d | queries x keys | pairs per head | forward ms | backward ms | forward TFLOP/s | backward TFLOP/s | "
              "total TFLOP/s | % of 2516.6 |", "|---|---|---|---|---|---|---|---|---|---|"]
-    for c in cases:
+    def row(c, label=None):
         f, b = measure(c)
         fl = c.head_dim * c.pairs * c.num_q_heads / 1e9
         tot = 14 * fl / (f + b)
-        lines.append(f"| {c.name} | {c.num_q_heads}/{c.num_kv_heads}, {c.head_dim} | {c.total_q} x {c.total_kv} | {c.pairs} | {f:.3f} | {b:.3f} | "
+        lines.append(f"| {label or c.name} | {c.num_q_heads}/{c.num_kv_heads}, {c.head_dim} | {c.total_q} x {c.total_kv} | {c.pairs} | {f:.3f} | {b:.3f} | "
                      f"{4 * fl / f:.1f} | {10 * fl / b:.1f} | {tot:.1f} | {100 * tot / PEAK:.1f} |")
         print(lines[-1], flush=True)
+
+    for c in cases:
+        row(c)
+    if args.variants:
+        for base in (cases[3], cases[5]):
+            for d in (64, 96, 256):
+                row(dataclasses.replace(base, head_dim=d), f"{base.name}, head_dim {d}")
+            ca.chunk_attn_test_set_bwd_mode(2)
+            try:
+                row(base, f"{base.name}, one-pass backward")
+            finally:
+                ca.chunk_attn_test_set_bwd_mode(0)
     text = "\n".join(lines) + "\n"
     if args.markdown:
         with open(args.markdown, "w") as fh:

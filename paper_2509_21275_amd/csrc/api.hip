@@ -158,7 +158,8 @@ void layout_fwd(const chunk_attn_desc* d, FwdLayout& L, bool with_plan) {
   L.jobs_off = align_up(L.items_bytes);
   L.blocks = (int64_t)n_items * d->num_kv_heads * (group / heads_per_wg(group, fwd_waves(d->head_dim)));
   L.flags_off = align_up(L.jobs_off + (size_t)L.kv_tiles * sizeof(TileJob));
-  L.blob_bytes = L.flags_off + ((size_t)L.blocks + 1) * sizeof(int32_t);  // one flag per workgroup, then "any flag raised"
+  // one flag per block, then "any flag raised", then the block-queue counters of the pipelined kernel (all zero)
+  L.blob_bytes = L.flags_off + ((size_t)L.blocks + 1 + kBlockQueues) * sizeof(int32_t);
   L.vt_off = align_up(L.blob_bytes);
   L.total = L.vt_off + align_up((size_t)L.kv_tiles * d->num_kv_heads * d->head_dim * 64 * sizeof(__bf16));
 }
@@ -469,6 +470,7 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
   p.redo = desc->head_dim == 128 ? reinterpret_cast<int32_t*>(ws + L.flags_off) : nullptr;
   p.any_redo = reinterpret_cast<int32_t*>(ws + L.flags_off) + L.blocks;
+  p.taken = p.any_redo + 1;
   p.ref_limit = g_fwd_rescale_limit.load();
   const int64_t blocks = L.blocks;
   if (blocks > 0x7fffffff) return CHUNK_ATTN_UNSUPPORTED;
@@ -517,7 +519,7 @@ int chunk_attn_fwd_static(const chunk_attn_desc* desc, const void* q, const void
   const int n_items = (int)(L.items_bytes / sizeof(FwdItem));
   hipLaunchKernelGGL(plan_fwd_static_kernel, dim3(1), dim3(256), 0, stream, segs, desc->num_segments, L.tile_rows,
                      reinterpret_cast<FwdItem*>(ws), n_items, reinterpret_cast<TileJob*>(ws + L.jobs_off), (int)L.kv_tiles,
-                     reinterpret_cast<int32_t*>(ws + L.flags_off), (int)L.blocks + 1);
+                     reinterpret_cast<int32_t*>(ws + L.flags_off), (int)L.blocks + 1 + kBlockQueues);
   if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "schedule kernel launch");
 
   FwdParams p;
@@ -538,6 +540,7 @@ int chunk_attn_fwd_static(const chunk_attn_desc* desc, const void* q, const void
   p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
   p.redo = desc->head_dim == 128 ? reinterpret_cast<int32_t*>(ws + L.flags_off) : nullptr;
   p.any_redo = reinterpret_cast<int32_t*>(ws + L.flags_off) + L.blocks;
+  p.taken = p.any_redo + 1;
   p.ref_limit = g_fwd_rescale_limit.load();
   e = launch_fwd(p, desc->head_dim, (int)L.blocks, reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.kv_tiles, stream);
   if (e != hipSuccess) return hip_fail(e, "forward launch");

@@ -86,6 +86,7 @@ struct DqParams {
   int64_t total_kv32_tiles, total_q_tiles;
   int32_t num_q_heads, num_kv_heads, group, heads_per_wg, head_splits;
   float scale, scale_log2;
+  int32_t* taken;        // 8 block-queue counters of the pipelined kernel (zero before the launch)
 };
 
 template <int D, int WAVES>
@@ -321,6 +322,7 @@ struct DkvParams {
   float scale, scale_log2;
   int32_t accumulate;
   int32_t out_f32;      // dk / dv point to fp32 arrays of the same shape
+  int32_t* taken;       // 8 block-queue counters of the pipelined kernel (zero before the launch)
 };
 
 // Four consecutive elements of a dK / dV row: stored, or added to what is there, as bf16 or as fp32.
@@ -654,7 +656,7 @@ __global__ __launch_bounds__(KB * 128, D > 128 ? 1 : 4 / KB) void bwd_dkv_kernel
 // MFMAs are written as opaque instructions.
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
+__global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int num_blocks) {
   constexpr int NW = 4;        // waves
   constexpr int BM = 32;       // query rows per stage
   constexpr int KC = D / 8;    // 16-byte chunks per operand row
@@ -687,8 +689,19 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
   const int role = wave >> 1, pair = wave & 1;
   const int l32 = lane & 31, hh = lane >> 5;
 
-  const int kvh = blockIdx.x % p.num_kv_heads;
-  const DkvItem it = p.items[blockIdx.x / p.num_kv_heads];
+  // The workgroup is persistent: it claims one block (128 keys of one key/value head) after the other
+  // (device_common.hpp) until none is left.  The next block is claimed when the current one's steps are done (claiming
+  // earlier would fix the order of the blocks before it is known which workgroup is free first) and the answer travels
+  // while the results are stored.
+  __shared__ int next_block;
+  const int xcd = xcd_of_this_wave();
+  int blk = 0;
+  if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
+  blk = broadcast_from_wave0(&next_block, blk);
+  while (blk >= 0) {
+  int pending_claim = 0;
+  const int kvh = blk % p.num_kv_heads;
+  const DkvItem it = p.items[blk / p.num_kv_heads];
   const int G = p.group;
   const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
   const float c = p.scale_log2;
@@ -1057,6 +1070,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
       step(g, x[0], x[1], f[0], f[1]);
       step(g + 1, x[1], x[0], f[1], f[0]);
     }
+    // every copy of this wave has landed (the last ones rewrote a slot nobody reads): once all waves have met at the
+    // barrier that hands out the next block, the ring may be filled again
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
 
     // ---- epilogue: dV = dV^T (role A), dK = scale * dK^T (role B), written (or added) as bf16 ----
 #pragma unroll
@@ -1078,6 +1095,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
   };
   if (role == 0) body(std::integral_constant<int, 0>{});
   else body(std::integral_constant<int, 1>{});
+  // on to the next block; the stores of the epilogue are not waited for here
+  int nb = 0;
+  if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
+  blk = broadcast_from_wave0(&next_block, nb);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1096,7 +1118,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p) {
 // walk) or lies past the end run a second variant of the step that masks in the vector work.
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
+__global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num_blocks) {
   constexpr int NW = 4;        // waves
   constexpr int BN = 32;       // key rows per stage
   constexpr int KC = D / 8;    // 16-byte chunks per K / V row
@@ -1120,9 +1142,19 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
 
+  // The workgroup is persistent: it claims one block (work item x key/value head x head split) after the other
+  // (device_common.hpp) until none is left.  The next block is claimed when the current one's steps are done (claiming
+  // earlier would fix the order of the blocks before it is known which workgroup is free first) and the answer travels
+  // while the results are stored.
+  __shared__ int next_block;
+  const int xcd = xcd_of_this_wave();
+  int blk = 0;
+  if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
+  blk = broadcast_from_wave0(&next_block, blk);
+  while (blk >= 0) {
   const int inner_n = p.num_kv_heads * p.head_splits;
-  const int inner = blockIdx.x % inner_n;
-  const DqItem it = p.items[blockIdx.x / inner_n];
+  const int inner = blk % inner_n;
+  const DqItem it = p.items[blk / inner_n];
   const int kvh = inner % p.num_kv_heads, hs = inner / p.num_kv_heads;
   int head[2], row0[2];  // of the wave's two units
 #pragma unroll
@@ -1149,30 +1181,6 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
       lds_store8(L + V_OFF + (DIST + 1) * KT + x * 8, z);
     }
   }
-
-  // Q and dO fragments (B operands): lane holds X[row = l32 of the unit][16 ks + 8 hh ..+7]; LSE and D of that row
-  bf16x8 qf[2][DK], gf[2][DK];
-  float lse2[2], dsum[2];
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r_own = min(row0[u] + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
-    const int64_t off = (int64_t)(it.q_row0 + r_own) * q_stride + (int64_t)head[u] * D + 8 * hh;
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      qf[u][ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
-      gf[u][ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
-    }
-    const int64_t slot = (int64_t)head[u] * p.total_q_tiles * 64 + it.q_slot0 + r_own;
-    lse2[u] = p.lse2p[slot];
-    dsum[u] = p.dsp[slot];
-  }
-  // -D of the unit's row in every element of a tile: the accumulation of dP^T starts from it, so that the vector work
-  // gets dP - D straight from the matrix pipe (a column of dP^T belongs to one query row)
-  f32x16 dneg[2];
-#pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) dneg[u][i] = dsum[u];
 
   // ---- staging: the 2 NP pieces of a stage (NP of K, then NP of V) are dealt to the waves round robin; a piece is
   // 64 consecutive slots of a chunk-major tile = two chunk columns of 32 rows.  Past the last stage the last one is
@@ -1233,16 +1241,39 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
 
-  // A wait the compiler can see for the loads above, before the first copy is issued (see bwd_dkv_pipe_kernel)
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-  // prologue: stages 0 .. DIST; stages 0 and 1 must have landed before the first step
+  // prologue: the copies of stages 0 .. DIST first, then the fragments, so that both travel at the same time
 #pragma unroll
   for (int s = 0; s <= DIST; ++s) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) dma_piece(i);
     dma_advance();
   }
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * PER) : "memory");
+  // Q and dO fragments (B operands): lane holds X[row = l32 of the unit][16 ks + 8 hh ..+7]; LSE and D of that row
+  bf16x8 qf[2][DK], gf[2][DK];
+  float lse2[2], dsum[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int r_own = min(row0[u] + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
+    const int64_t off = (int64_t)(it.q_row0 + r_own) * q_stride + (int64_t)head[u] * D + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      qf[u][ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
+      gf[u][ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
+    }
+    const int64_t slot = (int64_t)head[u] * p.total_q_tiles * 64 + it.q_slot0 + r_own;
+    lse2[u] = p.lse2p[slot];
+    dsum[u] = p.dsp[slot];
+  }
+  // -D of the unit's row in every element of a tile: the accumulation of dP^T starts from it, so that the vector work
+  // gets dP - D straight from the matrix pipe (a column of dP^T belongs to one query row)
+  f32x16 dneg[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dneg[u][i] = dsum[u];
+  // One wait the compiler can see for everything issued so far (loads complete in order: the copies have landed when
+  // the fragments have), so that it puts no full waits for outstanding loads into the loop
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
   wg_barrier();
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -1403,6 +1434,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
     step(t + 1, x[1], x[0], f[1], f[0], std::true_type{});
   }
 
+  // every copy of this wave has landed (the last ones rewrote a slot nobody reads): after the barrier below the next
+  // block may fill the ring again
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  int pending_claim = 0;
+  if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
   // ---- epilogue: dQ = scale * dQ^T ----
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
@@ -1418,6 +1454,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p) {
           *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * g + 4 * hh) = v;
         }
     }
+  }
+  // on to the next block; the stores above are not waited for here
+  int nb = 0;
+  if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
+  blk = broadcast_from_wave0(&next_block, nb);
   }
 }
 
@@ -1484,13 +1525,14 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.heads_per_wg = heads_per_wg(group, dq_waves(D)); p.head_splits = group / p.heads_per_wg;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
+    p.taken = reinterpret_cast<int32_t*>(ws + P.queues_off);
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if constexpr (D == 128) {
       const size_t smem = (size_t)2 * (DQ_PIPE_DIST + 3) * 32 * D * 2;  // ring slots of a K and a V tile
       static const hipError_t attr = raise_smem_limit(&bwd_dq_pipe_kernel<D>, smem);
       if (attr != hipSuccess) return attr;
-      hipLaunchKernelGGL((bwd_dq_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+      hipLaunchKernelGGL((bwd_dq_pipe_kernel<D>), dim3((unsigned)persistent_grid(blocks)), dim3(256), smem, stream, p, (int)blocks);
     } else {
       const size_t smem = (size_t)9 * 32 * D * 2;  // 3 stages of K, V and K^T tiles
       constexpr int DQW = 4;
@@ -1510,6 +1552,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.accumulate = a.accumulate ? 1 : 0;
     p.out_f32 = a.dkv_f32 ? 1 : 0;
+    p.taken = reinterpret_cast<int32_t*>(ws + P.queues_off) + kBlockQueues;
     static_assert(DKV_KEYS == 128, "the head_dim 64 and 128 kernels cover 128 keys per workgroup");
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
@@ -1522,7 +1565,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
       static const hipError_t attr = raise_smem_limit(&bwd_dkv_pipe_kernel<D>, smem);
       if (attr != hipSuccess) return attr;
       if (pe.start && (e = hipEventRecord(pe.start, stream)) != hipSuccess) return e;
-      hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+      hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D>), dim3((unsigned)persistent_grid(blocks)), dim3(256), smem, stream, p, (int)blocks);
     } else {
       // 4 ring slots of two 32-row operand tiles, 2 P hand-over slots, 4 slots of LSE and D rows
       constexpr int KB = (D > 128 ? 64 : DKV_KEYS) / 32;   // as dkv_keys(D)
@@ -1573,7 +1616,9 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   const size_t n_fused = d->head_dim == 128 ? n_dkv_blocks(d) * (size_t)d->num_kv_heads : 0;
   P.forder_off = P.fitems_off + up256(n_fused * sizeof(FusedItem));
   P.q32jobs_off = P.forder_off + up256(n_fused * kNumXcd * sizeof(int32_t));
-  P.blob_bytes = P.q32jobs_off + (d->head_dim == 128 ? up256((size_t)P.qt32_tiles * sizeof(DqTileJob)) : 0);
+  // block-queue counters of the dQ and of the dK/dV kernel (zero in the blob)
+  P.queues_off = P.q32jobs_off + (d->head_dim == 128 ? up256((size_t)P.qt32_tiles * sizeof(DqTileJob)) : 0);
+  P.blob_bytes = P.queues_off + up256(2 * kBlockQueues * sizeof(int32_t));
   const size_t row_slots = (size_t)d->num_q_heads * P.q_tiles * 64;
   P.fprog_off = P.blob_bytes;
   // progress counters, then the status word (its own 256 bytes), then a scratch tile

@@ -70,4 +70,59 @@ __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
 }
 
+// ---- dynamic assignment of a launch's blocks to persistent workgroups ----
+// A launch has `total` blocks of work (what used to be one workgroup each).  They are dealt to eight queues by index
+// modulo 8: a grid's workgroup b runs on XCD b % 8, so the host's block order already puts blocks that share data
+// (the same key/value head) on one XCD, whose L2 then serves the stream they share.  One workgroup per CU is launched;
+// it takes blocks from the queue of the XCD it runs on, front to back (the host sorts blocks longest first), and once
+// that queue is empty from the queue with the most blocks left.  The XCDs of a chip do not run at the same speed (their
+// finishing times differed by 4 - 7 % with a fixed share each); this way the fast ones take over what the slow ones
+// have not started, and only the blocks taken over lose their L2 neighbourhood.  `taken` (device, 8 counters, zero when
+// the kernel starts) counts the claims per queue; an index past the end of a queue means it is empty.  No workgroup
+// ever waits for another one.
+__device__ __forceinline__ int xcd_of_this_wave() { return __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & 7; }
+__device__ __forceinline__ int block_queue_len(int total, int x) { return total > x ? (total - x + 7) >> 3 : 0; }
+// Claim of the next block of queue x, issued by lane 0 without waiting for the answer (the caller reads `idx` later).
+__device__ __forceinline__ int block_claim_issue(int32_t* taken, int x) {
+  int idx = 0;
+  if ((threadIdx.x & 63) == 0) idx = __hip_atomic_fetch_add(taken + x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return idx;
+}
+// Turns the answer of block_claim_issue into a block index, or finds a block in another queue; -1: nothing is left.
+// Called by one whole wave; the result is wave-uniform.
+__device__ __forceinline__ int block_claim_finish(int32_t* taken, int total, int x, int idx) {
+  idx = __builtin_amdgcn_readfirstlane(idx);
+  if (idx < block_queue_len(total, x)) return x + 8 * idx;
+  const int lane = threadIdx.x & 63;
+  // a failed claim proves its queue empty for good (the counters only grow), so eight rounds see every queue empty
+  for (int round = 0; round < 8; ++round) {
+    int left = 0;
+    if (lane < 8)
+      left = block_queue_len(total, lane) - __hip_atomic_load(taken + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int best = 0, y = -1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int l = __builtin_amdgcn_readlane(left, i);
+      if (l > best) {
+        best = l;
+        y = i;
+      }
+    }
+    if (y < 0) return -1;
+    idx = __builtin_amdgcn_readfirstlane(block_claim_issue(taken, y));
+    if (idx < block_queue_len(total, y)) return y + 8 * idx;
+  }
+  return -1;
+}
+// Hands a wave-uniform value of wave 0 to the whole workgroup through `slot` (LDS).  Contains a workgroup barrier
+// without a memory fence: outstanding global stores are not waited for.
+__device__ __forceinline__ int broadcast_from_wave0(int* slot, int value) {
+  if (threadIdx.x == 0) *(volatile int*)slot = value;
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  return __builtin_amdgcn_readfirstlane(*(volatile int*)slot);
+}
+
 }  // namespace chunk_attn

@@ -284,7 +284,7 @@ __global__ __launch_bounds__(WAVES * 64, D > 128 ? 1 : 8 / WAVES) void fwd_kerne
 // the step that masks in the vector work.
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
+__global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_blocks) {
   constexpr int NW = 4;        // waves
   constexpr int BN = 32;       // key rows per stage
   constexpr int KC = D / 8;    // 16-byte chunks per K / V row
@@ -308,9 +308,19 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
 
+  // The workgroup is persistent: it claims one block (work item x key/value head x head split) after the other
+  // (device_common.hpp) until none is left.  The next block is claimed when the current one's steps are done (claiming
+  // earlier would fix the order of the blocks before it is known which workgroup is free first) and the answer travels
+  // while the results are stored.
+  __shared__ int next_block;
+  const int xcd = xcd_of_this_wave();
+  int blk = 0;
+  if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
+  blk = broadcast_from_wave0(&next_block, blk);
+  while (blk >= 0) {
   const int inner_n = p.num_kv_heads * p.head_splits;
-  const int inner = blockIdx.x % inner_n;
-  const FwdItem it = p.items[blockIdx.x / inner_n];
+  const int inner = blk % inner_n;
+  const FwdItem it = p.items[blk / inner_n];
   const int kvh = inner % p.num_kv_heads, hs = inner / p.num_kv_heads;
   const int head = kvh * p.group + hs * p.heads_per_wg + wave % p.heads_per_wg;
   const int wave_row0 = (wave / p.heads_per_wg) * 64;  // the wave's units are rows wave_row0 + 32 u .. + 31 of `head`
@@ -331,16 +341,6 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
       lds_store8(L + K_OFF + (DIST + 1) * KT + x * 8, z);
       lds_store8(L + V_OFF + (DIST + 1) * KT + x * 8, z);
     }
-  }
-
-  // Q fragments (B operands of S^T = K Q^T): lane holds Q[row = l32 of the unit][16 ks + 8 hh ..+7]
-  bf16x8 qf[2][DK];
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = min(wave_row0 + 32 * u + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
-    const __bf16* qp = p.q + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D + 8 * hh;
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) qf[u][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
 
   // ---- staging: the 2 NP pieces of a stage (NP of K, then NP of V) are dealt to the waves round robin; a piece is
@@ -401,17 +401,25 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
 
-  // A wait the compiler can see for the loads above, before the first copy is issued: it then has no reason to put
-  // full waits for outstanding loads into the loop.
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-  // prologue: stages 0 .. DIST; stages 0 and 1 must have landed before the first step
+  // prologue: the copies of stages 0 .. DIST first, then the Q fragments, so that both travel at the same time
 #pragma unroll
   for (int s = 0; s <= DIST; ++s) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) dma_piece(i);
     dma_advance();
   }
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * PER) : "memory");
+  // Q fragments (B operands of S^T = K Q^T): lane holds Q[row = l32 of the unit][16 ks + 8 hh ..+7]
+  bf16x8 qf[2][DK];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int r = min(wave_row0 + 32 * u + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
+    const __bf16* qp = p.q + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) qf[u][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+  }
+  // One wait the compiler can see for everything issued so far (loads complete in order, so the copies have landed when
+  // the fragments have): it then has no reason to put full waits for outstanding loads into the loop.
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
   wg_barrier();
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -587,8 +595,13 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
     step(t, x[0], x[1], f[0], f[1], std::true_type{});
     step(t + 1, x[1], x[0], f[1], f[0], std::true_type{});
   }
+  // every copy of this wave has landed (the last ones rewrote a slot nobody reads): after the barrier below the next
+  // block may fill the ring again
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  int pending_claim = 0;
+  if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
   if (__any(risk) && lane == 0) {
-    p.redo[blockIdx.x] = 1;
+    p.redo[blk] = 1;
     *p.any_redo = 1;
   }
 
@@ -610,6 +623,11 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p) {
         }
       if (hh == 0) p.lse[(int64_t)head * p.total_q + it.q_row0 + r] = (mc[u] + log2f(l_tot)) * 0.6931471805599453f;
     }
+  }
+  // on to the next block; the stores above are not waited for here
+  int nb = 0;
+  if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
+  blk = broadcast_from_wave0(&next_block, nb);
   }
 }
 
@@ -638,7 +656,7 @@ hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, const Ti
   const size_t smem = (size_t)2 * (FWD_PIPE_DIST + 3) * 32 * 128 * 2;  // ring slots of a K and a V tile
   static const hipError_t attr = raise_smem_limit(&fwd_pipe_kernel<128>, smem);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((fwd_pipe_kernel<128>), dim3(num_blocks), dim3(256), smem, stream, p);
+  hipLaunchKernelGGL((fwd_pipe_kernel<128>), dim3(persistent_grid(num_blocks)), dim3(256), smem, stream, p, num_blocks);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // Second pass over the same items, 8 waves of 32 rows: a workgroup returns at once unless its flag is raised, and the
   // transposed V images it reads are only made if any flag is.

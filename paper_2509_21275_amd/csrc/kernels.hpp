@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "device_common.hpp"
 #include "plan.hpp"
 
@@ -28,6 +30,7 @@ struct FwdParams {
   int32_t* redo;                             // per-workgroup redo flags of the pipelined forward (null: run every item)
   int32_t* any_redo;                         // raised together with any redo flag (gates the second pass's preparation)
   float ref_limit;                           // log2 growth of the row maximum past the first tile's that raises the flag
+  int32_t* taken;                            // 8 block-queue counters of the pipelined forward (zero before the launch)
 };
 
 // rows of query tile per forward work item for a given head layout
@@ -46,6 +49,17 @@ inline int heads_per_wg(int group, int waves) {
 // key rows per work item of the dK/dV kernel (32 per pair of waves); head_dim 256 leaves room for two pairs only
 inline int dkv_keys(int head_dim) { return head_dim > 128 ? 64 : DKV_KEYS; }
 inline int tile_rows(int group, int waves) { return 32 * (waves / heads_per_wg(group, waves)); }
+
+// Workgroups launched by a kernel whose workgroups claim their blocks themselves (device_common.hpp): one per CU of the
+// current device, and never more than there are blocks.
+inline int persistent_grid(int64_t blocks) {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      cus <= 0)
+    cus = 256;
+  return (int)std::max<int64_t>(1, std::min<int64_t>(blocks, cus));
+}
+constexpr int kBlockQueues = 8;  // counters per kernel that claims its blocks
 
 // Events armed by chunk_attn_profile_events for the calling thread (null when disarmed).
 struct ProfileEvents {
@@ -71,7 +85,7 @@ struct BwdPlan {
   std::vector<DkvItem> dkv_items;
   std::vector<TileJob> qjobs, kjobs;
   int64_t q_tiles = 0, kv32_tiles = 0;
-  size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, blob_bytes = 0;
+  size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, queues_off = 0, blob_bytes = 0;
   size_t lse2p_off = 0, dsp_off = 0, kt_off = 0, total = 0;
   // one-pass backward (head_dim 128): its items and workgroup order travel at the end of the blob; then the per-wave
   // progress counters and the status word (cleared by a kernel on every call) and the float32 dQ tiles
