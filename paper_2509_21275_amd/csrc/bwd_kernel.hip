@@ -690,9 +690,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   const int l32 = lane & 31, hh = lane >> 5;
 
   // The workgroup is persistent: it claims one block (128 keys of one key/value head) after the other
-  // (device_common.hpp) until none is left.  The next block is claimed when the current one's steps are done (claiming
-  // earlier would fix the order of the blocks before it is known which workgroup is free first) and the answer travels
-  // while the results are stored.
+  // (device_common.hpp) until none is left.  The next block is claimed before the current one's last few steps: early
+  // enough for the answer to arrive by the time it is needed, and not earlier (that would fix the order of the blocks
+  // before it is known which workgroup is free first).
   __shared__ int next_block;
   const int xcd = xcd_of_this_wave();
   int blk = 0;
@@ -1066,14 +1066,15 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
     };
     // role A's last product is dV^T of stage n - 1 in step n + 1, role B's dK^T of stage n - 1 in step n + 3
     const int n_steps = n_iter + 4;
+    const int claim_at = max(0, n_steps - 4) & ~1;  // the step pair before which wave 0 claims the next block
     for (int g = 0; g < n_steps; g += 2) {
+      if (g == claim_at && wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
       step(g, x[0], x[1], f[0], f[1]);
       step(g + 1, x[1], x[0], f[1], f[0]);
     }
     // every copy of this wave has landed (the last ones rewrote a slot nobody reads): once all waves have met at the
     // barrier that hands out the next block, the ring may be filled again
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-    if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
 
     // ---- epilogue: dV = dV^T (role A), dK = scale * dK^T (role B), written (or added) as bf16 ----
 #pragma unroll
@@ -1137,21 +1138,27 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
   lds_bf16* const L = (lds_bf16*)smem;
   constexpr int K_OFF = 0;               // [NS][KT]  K rows of stage n in slot n % NS (chunk-major)
   constexpr int V_OFF = K_OFF + NS * KT; // [NS][KT]  V rows
+  // [NW][64][D] staging of a wave's 64 rows of dQ on their way out, rows of 16-byte chunks, swizzled (tile_elem<KC>):
+  // global memory is then written in whole rows (four per instruction) instead of 32 rows with 16 bytes each, which
+  // costs the address unit several times as long.  Its first word doubles as the slot through which wave 0 announces
+  // the next block, between the last read of one block and the first write of the next.
+  constexpr int ST_OFF = V_OFF + NS * KT;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
+  int* const next_block = (int*)((__bf16*)smem + ST_OFF);
 
   // The workgroup is persistent: it claims one block (work item x key/value head x head split) after the other
-  // (device_common.hpp) until none is left.  The next block is claimed when the current one's steps are done (claiming
-  // earlier would fix the order of the blocks before it is known which workgroup is free first) and the answer travels
-  // while the results are stored.
-  __shared__ int next_block;
+  // (device_common.hpp) until none is left.  The next block is claimed before the current one's last few steps: early
+  // enough for the answer to arrive by the time it is needed, and not earlier (that would fix the order of the blocks
+  // before it is known which workgroup is free first).
   const int xcd = xcd_of_this_wave();
   int blk = 0;
   if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
-  blk = broadcast_from_wave0(&next_block, blk);
+  blk = broadcast_from_wave0(next_block, blk);
   while (blk >= 0) {
+  wg_barrier();  // every wave has read the announcement: the staging area may be written again
   const int inner_n = p.num_kv_heads * p.head_splits;
   const int inner = blk % inner_n;
   const DqItem it = p.items[blk / inner_n];
@@ -1429,6 +1436,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
     step(t, x[0], x[1], f[0], f[1], std::false_type{});
     step(t + 1, x[1], x[0], f[1], f[0], std::false_type{});
   }
+  int pending_claim = 0;
+  if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
   for (; t <= nt; t += 2) {
     step(t, x[0], x[1], f[0], f[1], std::true_type{});
     step(t + 1, x[1], x[0], f[1], f[0], std::true_type{});
@@ -1437,28 +1446,37 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
   // every copy of this wave has landed (the last ones rewrote a slot nobody reads): after the barrier below the next
   // block may fill the ring again
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-  int pending_claim = 0;
-  if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
-  // ---- epilogue: dQ = scale * dQ^T ----
+  // ---- epilogue: dQ = scale * dQ^T, through the wave's staging tile (one unit after the other) ----
+  lds_bf16* const stage = L + ST_OFF + wave * (64 * D);
+  // (the lane index is made opaque here: the addresses below depend on nothing else, and computed ahead of the loop
+  // they would take registers the loop has no room for)
+  int lane_e = lane;
+  asm volatile("" : "+v"(lane_e));
+  const int l32_e = lane_e & 31, hh_e = lane_e >> 5;
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    const int r = row0[u] + l32;
-    if (r < it.q_rows) {
-      __bf16* op = p.dq + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head[u] * D;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const bf16x4 v = pack4(dq[u][db][4 * g] * p.scale, dq[u][db][4 * g + 1] * p.scale, dq[u][db][4 * g + 2] * p.scale,
-                                 dq[u][db][4 * g + 3] * p.scale);
-          *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * g + 4 * hh) = v;
-        }
+      for (int g = 0; g < 4; ++g) {
+        const bf16x4 v = pack4(dq[u][db][4 * g] * p.scale, dq[u][db][4 * g + 1] * p.scale, dq[u][db][4 * g + 2] * p.scale,
+                               dq[u][db][4 * g + 3] * p.scale);
+        *(__attribute__((address_space(3))) bf16x4*)(stage + tile_elem<KC>(32 * u + l32_e, 4 * db + g) + 4 * hh_e) = v;
+      }
+    __bf16* obase = p.dq + (int64_t)(it.q_row0 + row0[u]) * q_stride + (int64_t)head[u] * D;
+#pragma unroll 2
+    for (int i = 0; i < 32 * KC / 64; ++i) {
+      const int x = (u * 32 * KC / 64 + i) * 64 + lane_e;
+      const int row = x / KC, c = unswz<KC>(row, x % KC);  // row of the staging tile: 32 u + row of the unit
+      const bf16x8 v = lds_load8(stage + x * 8);
+      const int ru = row - 32 * u;
+      if (row0[u] + ru < it.q_rows) *reinterpret_cast<bf16x8*>(obase + (int64_t)ru * q_stride + c * 8) = v;
     }
   }
   // on to the next block; the stores above are not waited for here
   int nb = 0;
   if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
-  blk = broadcast_from_wave0(&next_block, nb);
+  blk = broadcast_from_wave0(next_block, nb);
   }
 }
 
@@ -1529,7 +1547,8 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if constexpr (D == 128) {
-      const size_t smem = (size_t)2 * (DQ_PIPE_DIST + 3) * 32 * D * 2;  // ring slots of a K and a V tile
+      // ring slots of a K and a V tile, then the staging tiles of the four waves (64 rows each)
+      const size_t smem = (size_t)2 * (DQ_PIPE_DIST + 3) * 32 * D * 2 + (size_t)4 * 64 * D * 2;
       static const hipError_t attr = raise_smem_limit(&bwd_dq_pipe_kernel<D>, smem);
       if (attr != hipSuccess) return attr;
       hipLaunchKernelGGL((bwd_dq_pipe_kernel<D>), dim3((unsigned)persistent_grid(blocks)), dim3(256), smem, stream, p, (int)blocks);

@@ -303,21 +303,29 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
   lds_bf16* const L = (lds_bf16*)smem;
   constexpr int K_OFF = 0;               // [NS][KT]  K rows of stage n in slot n % NS (chunk-major)
   constexpr int V_OFF = K_OFF + NS * KT; // [NS][KT]  V rows
+  // [NW][64][D] staging of a wave's 64 rows of Q on their way in and of O on their way out, rows of 16-byte chunks,
+  // swizzled (tile_elem<KC>): global memory is then touched in whole rows (four per instruction) instead of 32 rows
+  // with 32 bytes each, which costs the address unit eight times as long.  Its first word doubles as the slot through
+  // which wave 0 announces the next block, between the last read of one block and the first copy of the next.
+  constexpr int ST_OFF = V_OFF + NS * KT;
+  constexpr int ST_ROWS = 64;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
+  __bf16* const stage = (__bf16*)smem + ST_OFF + wave * (ST_ROWS * D);  // this wave's staging tile (generic pointer)
+  int* const next_block = (int*)((__bf16*)smem + ST_OFF);
 
   // The workgroup is persistent: it claims one block (work item x key/value head x head split) after the other
-  // (device_common.hpp) until none is left.  The next block is claimed when the current one's steps are done (claiming
-  // earlier would fix the order of the blocks before it is known which workgroup is free first) and the answer travels
-  // while the results are stored.
-  __shared__ int next_block;
+  // (device_common.hpp) until none is left.  The next block is claimed before the current one's last few steps: early
+  // enough for the answer to arrive by the time it is needed, and not earlier (that would fix the order of the blocks
+  // before it is known which workgroup is free first).
   const int xcd = xcd_of_this_wave();
   int blk = 0;
   if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
-  blk = broadcast_from_wave0(&next_block, blk);
+  blk = broadcast_from_wave0(next_block, blk);
   while (blk >= 0) {
+  wg_barrier();  // every wave has read the announcement: the staging area may be written again
   const int inner_n = p.num_kv_heads * p.head_splits;
   const int inner = blk % inner_n;
   const FwdItem it = p.items[blk / inner_n];
@@ -408,18 +416,27 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
     for (int i = 0; i < PER; ++i) dma_piece(i);
     dma_advance();
   }
+  // the wave's 64 rows of Q (its two units) into its staging tile: slot x = 16 row + position holds the chunk that
+  // belongs there; rows past the tile repeat the last one (never stored)
+  {
+    const __bf16* qbase = p.q + (int64_t)it.q_row0 * q_stride + (int64_t)head * D;
+#pragma unroll 4
+    for (int i = 0; i < ST_ROWS * KC / 64; ++i) {
+      const int x = i * 64 + lane;
+      const int row = x / KC, c = unswz<KC>(row, x % KC);
+      const int r = min(wave_row0 + row, it.q_rows - 1);
+      dma16(qbase + (int64_t)r * q_stride + c * 8, stage + i * 512);
+    }
+  }
+  // One wait the compiler can see for everything issued so far: it then has no reason to put full waits for outstanding
+  // loads into the loop.
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
   // Q fragments (B operands of S^T = K Q^T): lane holds Q[row = l32 of the unit][16 ks + 8 hh ..+7]
   bf16x8 qf[2][DK];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = min(wave_row0 + 32 * u + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
-    const __bf16* qp = p.q + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D + 8 * hh;
+  for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) qf[u][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-  }
-  // One wait the compiler can see for everything issued so far (loads complete in order, so the copies have landed when
-  // the fragments have): it then has no reason to put full waits for outstanding loads into the loop.
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    for (int ks = 0; ks < DK; ++ks) qf[u][ks] = lds_chunk<KC>(stage, 32 * u + l32, 2 * ks + hh);
   wg_barrier();
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -591,6 +608,8 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
     step(t, x[0], x[1], f[0], f[1], std::false_type{});
     step(t + 1, x[1], x[0], f[1], f[0], std::false_type{});
   }
+  int pending_claim = 0;
+  if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
   for (; t <= nt; t += 2) {
     step(t, x[0], x[1], f[0], f[1], std::true_type{});
     step(t + 1, x[1], x[0], f[1], f[0], std::true_type{});
@@ -598,36 +617,50 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
   // every copy of this wave has landed (the last ones rewrote a slot nobody reads): after the barrier below the next
   // block may fill the ring again
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-  int pending_claim = 0;
-  if (wave == 0) pending_claim = block_claim_issue(p.taken, xcd);
   if (__any(risk) && lane == 0) {
     p.redo[blk] = 1;
     *p.any_redo = 1;
   }
 
   // ---- epilogue: O = O^T / l, LSE = ln(l) + m scale ----
+  // (through the wave's staging tile: the lane that holds four values of a row writes them there, then every lane
+  // moves one 16-byte chunk of a row to global memory, four whole rows per instruction; one unit after the other, so
+  // that few values are in flight at a time)
+  {
+    // (the lane index is made opaque here: the addresses below depend on nothing else, and computed ahead of the loop
+    // they would take registers for its whole length)
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int l32_e = lane_e & 31, hh_e = lane_e >> 5;
+    __bf16* obase = p.o + (int64_t)it.q_row0 * q_stride + (int64_t)head * D;
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = wave_row0 + 32 * u + l32;
-    const float l_tot = sum_halves(l_run[u]);
-    if (r < it.q_rows) {
+    for (int u = 0; u < 2; ++u) {
+      const int r = wave_row0 + 32 * u + l32_e;
+      const float l_tot = sum_halves(l_run[u]);
       const float inv = 1.0f / l_tot;
-      __bf16* op = p.o + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const bf16x4 v = pack4(oacc[u][db][4 * g] * inv, oacc[u][db][4 * g + 1] * inv, oacc[u][db][4 * g + 2] * inv,
                                  oacc[u][db][4 * g + 3] * inv);
-          *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * g + 4 * hh) = v;
+          *reinterpret_cast<bf16x4*>(stage + tile_elem<KC>(32 * u + l32_e, 4 * db + g) + 4 * hh_e) = v;
         }
-      if (hh == 0) p.lse[(int64_t)head * p.total_q + it.q_row0 + r] = (mc[u] + log2f(l_tot)) * 0.6931471805599453f;
+      if (r < it.q_rows && hh_e == 0)
+        p.lse[(int64_t)head * p.total_q + it.q_row0 + r] = (mc[u] + log2f(l_tot)) * 0.6931471805599453f;
+#pragma unroll 2
+      for (int i = 0; i < 32 * KC / 64; ++i) {
+        const int x = (u * 32 * KC / 64 + i) * 64 + lane_e;
+        const int row = x / KC, c = unswz<KC>(row, x % KC);
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + x * 8);
+        if (wave_row0 + row < it.q_rows) *reinterpret_cast<bf16x8*>(obase + (int64_t)(wave_row0 + row) * q_stride + c * 8) = v;
+      }
     }
   }
   // on to the next block; the stores above are not waited for here
   int nb = 0;
   if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
-  blk = broadcast_from_wave0(&next_block, nb);
+  blk = broadcast_from_wave0(next_block, nb);
   }
 }
 
@@ -653,7 +686,8 @@ hipError_t launch_fwd(const FwdParams& p, int head_dim, int num_blocks, const Ti
                               stream)) != hipSuccess) return e;
     return head_dim == 256 ? launch_fwd_t<256, 4>(p, num_blocks, stream) : launch_fwd_t<64, 4>(p, num_blocks, stream);
   }
-  const size_t smem = (size_t)2 * (FWD_PIPE_DIST + 3) * 32 * 128 * 2;  // ring slots of a K and a V tile
+  // ring slots of a K and a V tile, then the staging tiles of the four waves (64 rows each)
+  const size_t smem = (size_t)2 * (FWD_PIPE_DIST + 3) * 32 * 128 * 2 + (size_t)4 * 64 * 128 * 2;
   static const hipError_t attr = raise_smem_limit(&fwd_pipe_kernel<128>, smem);
   if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL((fwd_pipe_kernel<128>), dim3(persistent_grid(num_blocks)), dim3(256), smem, stream, p, num_blocks);
