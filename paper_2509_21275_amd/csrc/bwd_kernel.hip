@@ -630,6 +630,38 @@ __global__ __launch_bounds__(KB * 128, D > 128 ? 1 : 4 / KB) void bwd_dkv_kernel
   }
 }
 
+// LDS instructions of one step of bwd_dkv_pipe_kernel in program order, per wave role, and the waits that follow from
+// it.  Mini-step m issues the read of fragment m + 4 (two instructions for a transposed fragment: the first NT of a step;
+// fragments past the end are the next step's first ones), then E0(m) instructions after its first MFMA and E1(m) after
+// its second: role A spreads its four hand-over stores and four row-value reads over mini-steps 0 .. 3 (issued in one go
+// they keep the matrix pipe waiting), role B reads the hand-over in mini-step 0 and its row values in mini-step 1.
+// LDS operations of a wave complete in order, so "fragment m has arrived" = "at most wait(m) LDS instructions issued
+// since its read are outstanding".  The vector work starts in mini-step 4, which therefore also waits for the last of
+// the hand-over / row-value instructions.
+template <int ROLE, int NF, int NT>
+struct DkvLdsOrder {
+  static constexpr int cost(int k) { return ((k % NF + NF) % NF) < NT ? 2 : 1; }
+  static constexpr int e0(int m) { return ROLE == 0 ? (m < 4 ? 1 : 0) : (m < 2 ? 4 : 0); }
+  static constexpr int e1(int m) { return ROLE == 0 ? (m < 2 ? 2 : 0) : 0; }
+  static constexpr int after_fragment(int m) {
+    int n = m >= 4 ? e0(m - 4) + e1(m - 4) : 0;
+    for (int i = m - 3; i < m; ++i) n += cost(i + 4) + (i >= 0 ? e0(i) + e1(i) : 0);
+    return n;
+  }
+  static constexpr int after_extras() {  // instructions between the last E0 / E1 instruction and mini-step 4
+    int n = 0;
+    for (int i = 3; i >= 0; --i) {
+      if (e0(i) + e1(i) > 0) return n;  // nothing of mini-step i follows its last extra instruction
+      n += cost(i + 4);
+    }
+    return n;
+  }
+  static constexpr int wait(int m) {
+    const int a = after_fragment(m);
+    return m == 4 && after_extras() < a ? after_extras() : a;
+  }
+};
+
 // ------------------------------------------------------------------------------------------------
 // bwd_dkv_pipe (head_dim 128)
 //
@@ -886,19 +918,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
       });
     }
 
-    // LDS operations of a step, in program order: 8 for the hand-over and the row values, then one fragment per
-    // mini-step (two instructions for a transposed fragment: fragments 0 .. 2 DB - 1 of this step and of the next).
-    // Before mini-step m uses fragment m, everything issued up to its read must be complete; LGKM(m) is the number
-    // of LDS instructions issued after that read and before the wait (which precedes mini-step m's own read).
-    // In program order: mini-step m reads fragment m + 4 (two instructions for a transposed fragment, i.e. fragments
-    // 0 .. 7 of this step and 0 .. 3 of the next one, else one); mini-step 0 then issues the 4 hand-over instructions
-    // and mini-step 1 the 4 row-value reads.  lgkm_wait(m) = number of those instructions that lie between the read of
-    // fragment m and the start of mini-step m, where the wait stands (-1: an earlier wait already covers fragment m).
-    // Mini-step 4 also waits for the hand-over and the row values: only fragments 6 and 7 may be outstanding then.
-    auto lgkm_wait = [](int m) {
-      constexpr int tab[16] = {6, 10, 14, 14, 4, -1, 4, 3, 3, 3, 3, 3, 3, 4, 5, 6};
-      return tab[m];
-    };
+    using Lds = DkvLdsOrder<ROLE, NF, 2 * DB>;  // the waits for LDS data (see there)
     auto step = [&](int g, f32x16 (&cur)[2], f32x16 (&nxt)[2], bf16x8 (&f_old)[2][2],
                     bf16x8 (&f_new)[2][2]) __attribute__((always_inline)) {
       const int sR = prev_slot(sA), sT = prev_slot(sR);
@@ -923,8 +943,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
           mask_set = false;
         }
       }
-      // hand-over (mini-step 0) and row values (mini-step 1) are issued between the MFMAs, so that the matrix pipe
-      // restarts right after the barrier; the vector work starts at mini-step 4
+      // hand-over and row values are issued between the MFMAs of the first mini-steps, so that the matrix pipe restarts
+      // right after the barrier; the vector work starts at mini-step 4
       bf16x8 ph[2][2];
       f32x4 r4[4];  // LSE (role A) or -D (role B) of rows 8 g4 + 4 hh + 0..3
       const unsigned pa = pex0 + (ROLE == 0 ? (g & 1) : ((g & 1) ^ 1)) * (PS * 2);
@@ -970,15 +990,15 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
       static_for<0, NF>([&](auto m_c) __attribute__((always_inline)) {
         constexpr int m = decltype(m_c)::value;
         {  // wait for fragment m (and, in mini-step 4, for the hand-over and the row values)
-          constexpr int lgkm = lgkm_wait(m);
-          static_assert(lgkm <= 15, "lgkmcnt is a 4-bit counter");
+          constexpr int lgkm = Lds::wait(m);
+          static_assert(lgkm >= 0 && lgkm <= 15, "lgkmcnt is a 4-bit counter");
           if constexpr (m == 4) {
             if (ROLE == 0)
               asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(fr[m & 7]), "+v"(r4[0]), "+v"(r4[1]), "+v"(r4[2]), "+v"(r4[3]) : "n"(lgkm));
             else
               asm volatile("s_waitcnt lgkmcnt(%9)" : "+v"(fr[m & 7]), "+v"(r4[0]), "+v"(r4[1]), "+v"(r4[2]), "+v"(r4[3]),
                            "+v"(ph[0][0]), "+v"(ph[0][1]), "+v"(ph[1][0]), "+v"(ph[1][1]) : "n"(lgkm));
-          } else if constexpr (lgkm >= 0) {
+          } else {
             asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(fr[m & 7]) : "n"(lgkm));
           }
         }
@@ -1012,24 +1032,22 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
         constexpr std::integral_constant<int, 0> c0{};
         constexpr std::integral_constant<int, 1> c1{};
         mma(c0);
-        if constexpr (m == 0) {
-          if (ROLE == 0) {
-            lds_asm_write16<0>(pa, f_old[0][0]);
-            lds_asm_write16<1024>(pa, f_old[0][1]);
-            lds_asm_write16<2048>(pa, f_old[1][0]);
-            lds_asm_write16<3072>(pa, f_old[1][1]);
-          } else {
+        // hand-over and row values (DkvLdsOrder: E0)
+        if constexpr (ROLE == 0) {
+          if constexpr (m < 4) lds_asm_write16<1024 * m>(pa, f_old[m >> 1][m & 1]);
+        } else {
+          if constexpr (m == 0) {
             ph[0][0] = lds_asm_read16<0>(pa);
             ph[0][1] = lds_asm_read16<1024>(pa);
             ph[1][0] = lds_asm_read16<2048>(pa);
             ph[1][1] = lds_asm_read16<3072>(pa);
           }
-        }
-        if constexpr (m == 1) {
-          r4[0] = lds_asm_read16f<0>(ra);
-          r4[1] = lds_asm_read16f<32>(ra);
-          r4[2] = lds_asm_read16f<64>(ra);
-          r4[3] = lds_asm_read16f<96>(ra);
+          if constexpr (m == 1) {
+            r4[0] = lds_asm_read16f<0>(ra);
+            r4[1] = lds_asm_read16f<32>(ra);
+            r4[2] = lds_asm_read16f<64>(ra);
+            r4[3] = lds_asm_read16f<96>(ra);
+          }
         }
         if (m == 2) dma_rows();
         // pairs 0 .. 7 in mini-steps 4 .. 11 (one half next to each MFMA), pairs 8 .. 15 two per mini-step after that
@@ -1037,6 +1055,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
         if constexpr (m >= 12) vec_pair(std::integral_constant<int, 8 + 2 * (m - 12)>{});
         __builtin_amdgcn_sched_barrier(0);
         mma(c1);
+        if constexpr (ROLE == 0 && m < 2) {  // (E1)
+          r4[2 * m] = lds_asm_read16f<64 * m>(ra);
+          r4[2 * m + 1] = lds_asm_read16f<64 * m + 32>(ra);
+        }
         if (m >= 3 && m < 3 + 2 * PER && ((m - 3) & 1) == 0) dma_piece((m - 3) >> 1);
         if constexpr (m >= 4 && m < 12) vec_half(std::integral_constant<int, m - 4>{}, c1);
         if constexpr (m >= 12) vec_pair(std::integral_constant<int, 9 + 2 * (m - 12)>{});
@@ -1060,7 +1082,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
           f_new[kb][ks] = __builtin_bit_cast(bf16x8, v);
         }
       // Stage g + 1 must have landed; the copies of the DIST - 1 stages after it may still be in flight.  This wave's
-      // hand-over stores completed long ago (mini-step 2 waited for them).
+      // hand-over stores completed long ago (mini-step 4 waited for them).
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * (PER + 1)) : "memory");
       wg_barrier();
     };
