@@ -36,34 +36,38 @@ constexpr float kLog2e = 1.4426950408889634f;
 #endif
 
 // ------------------------------------------------------------------------------------------------
-// bwd_pre: one workgroup per (64-row query tile, head); 4 threads per row.
+// bwd_pre: one workgroup per (64-row query tile, head); D / 8 threads per row, one 16-byte chunk of O and of dO each, so
+// that a wave reads whole rows (the kernel is bound by memory: it reads O and dO once).
 // ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void bwd_pre_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o,
                                                       const float* __restrict__ lse, const TileJob* __restrict__ jobs,
                                                       int64_t total_q_tiles, int total_q, int num_q_heads,
                                                       float* __restrict__ lse2p, float* __restrict__ dsp) {
+  constexpr int TPR = D / 8;         // threads per row
+  constexpr int RPP = 256 / TPR;     // rows per pass
   const int head = blockIdx.x % num_q_heads;
   const TileJob job = jobs[blockIdx.x / num_q_heads];
-  const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
-  float acc = 0.f;
-  const bool valid = r < job.valid_rows;
-  if (valid) {
-    const int64_t base = ((int64_t)(job.src_row0 + r) * num_q_heads + head) * D + part * (D / 4);
+  const int part = threadIdx.x % TPR;
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + base + c * 8);
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(d_o + base + c * 8);
+  for (int pass = 0; pass < 64 / RPP; ++pass) {
+    const int r = pass * RPP + threadIdx.x / TPR;
+    const bool valid = r < job.valid_rows;
+    float acc = 0.f;
+    if (valid) {
+      const int64_t base = ((int64_t)(job.src_row0 + r) * num_q_heads + head) * D + part * 8;
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + base);
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(d_o + base);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
     }
-  }
-  acc += __shfl_xor(acc, 1);
-  acc += __shfl_xor(acc, 2);
-  if (part == 0) {
-    const int64_t slot = ((int64_t)head * total_q_tiles + job.image) * 64 + r;
-    dsp[slot] = valid ? -acc : 0.f;  // stored negated: the kernels add it (or start an accumulation from it)
-    lse2p[slot] = valid ? lse[(int64_t)head * total_q + job.src_row0 + r] * kLog2e : INFINITY;
+#pragma unroll
+    for (int w = 1; w < TPR; w *= 2) acc += __shfl_xor(acc, w);
+    if (part == 0) {
+      const int64_t slot = ((int64_t)head * total_q_tiles + job.image) * 64 + r;
+      dsp[slot] = valid ? -acc : 0.f;  // stored negated: the kernels add it (or start an accumulation from it)
+      lse2p[slot] = valid ? lse[(int64_t)head * total_q + job.src_row0 + r] * kLog2e : INFINITY;
+    }
   }
 }
 
