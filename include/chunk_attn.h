@@ -84,8 +84,8 @@ typedef struct {
 /*
  * Scratch sizes (bytes) for a descriptor: *fwd_bytes for chunk_attn_fwd, *bwd_bytes for
  * chunk_attn_bwd (the tile schedules, the row sums D_i = <dO_i, O_i>, and transposed
- * tile images of the operands).  Either output pointer may be NULL.  Validates the
- * descriptor.
+ * tile images of the operands; for head_dim 96 also zero-padded copies of the tensors, 128
+ * wide).  Either output pointer may be NULL.  Validates the descriptor.
  */
 int chunk_attn_workspace_bytes(const chunk_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
 

@@ -55,6 +55,26 @@ def test_valid_descriptors(ca):
     assert ca.chunk_attn_validate(desc(ca, [(0, 4, 3, 10), (4, 6, 20, 9)], tkv=40)) == ca.OK
 
 
+def test_head_dimensions(ca):
+    """64, 96, 128 and 256 are accepted; 96 runs as 128 on zero-padded copies kept in the workspace, so its workspace
+    is that of 128 plus the copies (Q, K, V, O for the forward; Q, K, V, O, dO, dQ and float32-sized dK, dV for the
+    backward)."""
+    segs = [(0, 300, 0, 500), (300, 212, 500, 212)]
+    sizes = {}
+    for d in (64, 96, 128, 256):
+        dd = desc(ca, segs, Hq=8, Hkv=2, d=d)
+        assert ca.chunk_attn_validate(dd) == ca.OK
+        assert ca.chunk_attn_pair_count(dd) == 300 * 200 + 300 * 301 // 2 + 212 * 213 // 2
+        sizes[d] = ca.chunk_attn_workspace_bytes(dd)
+    up = lambda x: (x + 255) // 256 * 256
+    qb, kb, gb = up(512 * 8 * 128 * 2), up(712 * 2 * 128 * 2), up(712 * 2 * 128 * 4)
+    assert sizes[96][0] == sizes[128][0] + 2 * qb + 2 * kb
+    assert sizes[96][1] == sizes[128][1] + 4 * qb + 2 * kb + 2 * gb
+    for d in (32, 80, 192, 512):
+        assert ca.chunk_attn_validate(desc(ca, segs, d=d)) == ca.UNSUPPORTED
+    assert "64, 96, 128 or 256" in ca.chunk_attn_strerror(ca.UNSUPPORTED)
+
+
 @pytest.mark.parametrize("segs,kw,code", [
     ([(0, 0, 0, 4)], {"tq": 4}, "BAD_SEGMENT"),                        # empty query range
     ([(0, 8, 0, 4)], {}, "BAD_SEGMENT"),                          # fewer keys than queries
