@@ -31,7 +31,8 @@
  * void*; NULL is the default stream) and return.  The segment table is a HOST pointer and
  * is only read during the call.  The library allocates no device memory: scratch space is
  * the caller's `workspace` (device memory, 256-byte aligned, at least the size reported by
- * chunk_attn_workspace_bytes).  Every tensor pointer must be 16-byte aligned (lse: 4-byte),
+ * chunk_attn_workspace_bytes; its contents need not survive between calls, and calls that
+ * may run at the same time, on different streams, need a workspace each).  Every tensor pointer must be 16-byte aligned (lse: 4-byte),
  * else CHUNK_ATTN_INVALID_ARG.  Functions return CHUNK_ATTN_OK (0) or a negative code and
  * never throw or abort; argument errors are detected on the host before anything is
  * launched.
