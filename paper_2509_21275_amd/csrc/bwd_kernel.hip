@@ -665,6 +665,14 @@ struct DkvLdsOrder {
     return m == 4 && after_extras() < a ? after_extras() : a;
   }
 };
+// (pins: the counts worked out by hand for head_dim 128, where a step has 16 fragments of which the first 8 are transposed)
+static_assert(DkvLdsOrder<1, 16, 8>::wait(0) == 6 && DkvLdsOrder<1, 16, 8>::wait(1) == 10 && DkvLdsOrder<1, 16, 8>::wait(2) == 14 &&
+              DkvLdsOrder<1, 16, 8>::wait(3) == 14 && DkvLdsOrder<1, 16, 8>::wait(4) == 4 && DkvLdsOrder<1, 16, 8>::wait(6) == 4 &&
+              DkvLdsOrder<1, 16, 8>::wait(7) == 3 && DkvLdsOrder<1, 16, 8>::wait(12) == 3 && DkvLdsOrder<1, 16, 8>::wait(13) == 4 &&
+              DkvLdsOrder<1, 16, 8>::wait(14) == 5 && DkvLdsOrder<1, 16, 8>::wait(15) == 6, "role B");
+static_assert(DkvLdsOrder<0, 16, 8>::wait(0) == 6 && DkvLdsOrder<0, 16, 8>::wait(1) == 9 && DkvLdsOrder<0, 16, 8>::wait(2) == 12 &&
+              DkvLdsOrder<0, 16, 8>::wait(3) == 13 && DkvLdsOrder<0, 16, 8>::wait(4) == 0 && DkvLdsOrder<0, 16, 8>::wait(6) == 6 &&
+              DkvLdsOrder<0, 16, 8>::wait(7) == 4 && DkvLdsOrder<0, 16, 8>::wait(8) == 3 && DkvLdsOrder<0, 16, 8>::wait(15) == 6, "role A");
 
 // ------------------------------------------------------------------------------------------------
 // bwd_dkv_pipe (head_dim 128)
