@@ -714,9 +714,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   constexpr int PS = 2 * 4 * 64 * 8;   // elements of one P hand-over slot: 2 wave pairs x 4 fragments x 64 lanes x 8
   constexpr int CH = BM * KC;          // 16-byte chunks per operand tile
   constexpr int NP = CH / 64;          // 64-slot pieces per tile
-  constexpr int PER = 2 * NP / NW;     // global->LDS copies of operand pieces per wave and stage
+  // global->LDS copies per wave and stage: the 2 NP operand pieces and the two sets of row values (LSE, D) are dealt
+  // unevenly, because issuing a copy costs a wave about as long as an MFMA and role A (the exponentials) is the one the
+  // step waits for: a role A wave copies two pieces and one set of row values, a role B wave six pieces
+  constexpr int PER_A = 2, PER_B = (2 * NP - 2 * PER_A) / 2;  // pieces per wave
+  constexpr int CPS_A = PER_A + 1, CPS_B = PER_B;              // copies per wave and stage
   constexpr int RV = 64;               // floats per slot of the LSE / D rows (32 used; a whole wave copies them)
-  static_assert(D == 128 && NF == 16 && PER == 4, "the mini-step schedule below is written for head_dim 128");
+  static_assert(D == 128 && NF == 16 && PER_B == 6, "the mini-step schedule below is written for head_dim 128");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   lds_bf16* const L = (lds_bf16*)smem;
@@ -765,18 +769,19 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   const int nqt = it.n_qt - it.qt_first;
   const int n_iter = nqt * G;  // stages: (head in group, query tile), head-major
 
-  // ---- staging (as in bwd_dkv_kernel): the 2 NP pieces of a stage are dealt to the waves round robin; even
-  // waves also copy the stage's LSE rows, odd waves its D rows (twice each: no wave-dependent branch).  Past the
-  // last stage the last one is copied again (into a slot nobody reads any more), so that every step issues the
-  // same number of copies. ----
-  // byte offset of the lane's chunk of piece i from the tile's first row, for a full tile and for the segment's
+  // ---- staging: copy i of a role A wave is piece `pair` of Q (i = 0) or of dO (i = 1), the first of the two waves
+  // also copies the stage's LSE rows, the second its D rows; copy i of a role B wave is piece 2 + 2 (i % 3) + pair of Q
+  // (i < 3) or of dO.  Past the last stage the last one is copied again (into a slot nobody reads any more), so
+  // that every step issues the same number of copies. ----
+  // byte offset of the lane's chunk of copy i from the tile's first row, for a full tile and for the segment's
   // last tile (rows past the last query repeat it; their P is 0)
-  unsigned v_full[PER], v_last[PER];
+  auto piece_in_tile = [&](int i) { return role == 0 ? pair : 2 + 2 * (i % 3) + pair; };
+  unsigned v_full[PER_B], v_last[PER_B];
   {
     const int last_row = it.q_len - 1 - (it.n_qt - 1) * BM;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int x = ((i * NW + wave) % NP) * 64 + lane;
+    for (int i = 0; i < PER_B; ++i) {
+      const int x = piece_in_tile(i) * 64 + lane;
       const int off = (x >> 5) * 8, row = (x & 31) ^ (((x >> 5) & 3) << 2);
       v_full[i] = (unsigned)(row * (int)q_stride + off) * 2u;
       v_last[i] = (unsigned)(min(row, last_row) * (int)q_stride + off) * 2u;
@@ -799,10 +804,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   lds_f32* const rows_dst = (wave & 1) ? dsum_s : lse_s;
   auto dma_rows = [&]() __attribute__((always_inline)) { dma4(d_r + lane4, rows_dst + d_slot / (QT / RV)); };
   auto dma_piece = [&](int i) __attribute__((always_inline)) {
-    const int piece = i * NW + wave;  // wave-uniform; i < NP / NW: a piece of Q, else of dO
+    const bool of_q = role == 0 ? i == 0 : i < PER_B / 2;
     const unsigned voff = d_left == 1 ? v_last[i] : v_full[i];  // the segment's last query tile
-    const char* base = i < NP / NW ? d_q : d_g;
-    lds_bf16* dst = L + (i < NP / NW ? Q_OFF + piece * 512 : G_OFF + (piece - NP) * 512) + d_slot;
+    const char* base = of_q ? d_q : d_g;
+    lds_bf16* dst = L + (of_q ? Q_OFF : G_OFF) + piece_in_tile(i) * 512 + d_slot;
     dma16(base + voff, dst);
   };
   auto dma_advance = [&]() __attribute__((always_inline)) {
@@ -864,13 +869,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
     const int jrel = it.j0 + 64 * pair + l32 - it.ctx;
     const int jrel_hi = it.j0 + 64 * pair + 63 - it.ctx;  // of the wave's last key
 
-    // prologue: stages 0 .. DIST - 1 (after the fragment loads, so that the waits below count only copies);
-    // every wave issues PER + 1 copies per stage
+    // prologue: stages 0 .. DIST - 1 (after the fragment loads, so that the waits below count only copies)
+    constexpr int CPS = ROLE ? CPS_B : CPS_A;      // copies of this wave per stage
+    constexpr int PIECES = ROLE ? PER_B : PER_A;
 #pragma unroll
     for (int s = 0; s < DIST; ++s) {
-      dma_rows();
+      if (ROLE == 0) dma_rows();
 #pragma unroll
-      for (int i = 0; i < PER; ++i) dma_piece(i);
+      for (int i = 0; i < PIECES; ++i) dma_piece(i);
       dma_advance();
     }
     // A wait the compiler can see, for all copies and loads issued so far: without it the compiler's own bookkeeping
@@ -1061,7 +1067,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
             r4[3] = lds_asm_read16f<96>(ra);
           }
         }
-        if (m == 2) dma_rows();
+        if (m == 2 && ROLE == 0) dma_rows();
         // pairs 0 .. 7 in mini-steps 4 .. 11 (one half next to each MFMA), pairs 8 .. 15 two per mini-step after that
         if constexpr (m >= 4 && m < 12) vec_half(std::integral_constant<int, m - 4>{}, c0);
         if constexpr (m >= 12) vec_pair(std::integral_constant<int, 8 + 2 * (m - 12)>{});
@@ -1071,10 +1077,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
           r4[2 * m] = lds_asm_read16f<64 * m>(ra);
           r4[2 * m + 1] = lds_asm_read16f<64 * m + 32>(ra);
         }
-        if (m >= 3 && m < 3 + 2 * PER && ((m - 3) & 1) == 0) dma_piece((m - 3) >> 1);
+        if (m >= 3 && m < 3 + 2 * PIECES && ((m - 3) & 1) == 0) dma_piece((m - 3) >> 1);
         if constexpr (m >= 4 && m < 12) vec_half(std::integral_constant<int, m - 4>{}, c1);
         if constexpr (m >= 12) vec_pair(std::integral_constant<int, 9 + 2 * (m - 12)>{});
-        if constexpr (m == 10) {  // bookkeeping for the next step (the copies of this step have been issued)
+        if constexpr (m == 14) {  // bookkeeping for the next step (the copies of this step have been issued)
           dma_advance();
           sA = sA == NS - 1 ? 0 : sA + 1;
           if (ROLE == 0 && ++s_qt == it.n_qt) s_qt = it.qt_first;
@@ -1095,7 +1101,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
         }
       // Stage g + 1 must have landed; the copies of the DIST - 1 stages after it may still be in flight.  This wave's
       // hand-over stores completed long ago (mini-step 4 waited for them).
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * (PER + 1)) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * CPS) : "memory");
       wg_barrier();
     };
     // role A's last product is dV^T of stage n - 1 in step n + 1, role B's dK^T of stage n - 1 in step n + 3
