@@ -149,3 +149,31 @@ def test_misaligned_tensor_pointers_are_rejected_on_the_host():
         args[i] = P(ts[i], 8)
         assert lib.chunk_attn_bwd(ctypes.byref(desc), *args, ctypes.c_int(0), P(ws), wsz, None) == ca.INVALID_ARG
     torch.cuda.synchronize()
+
+
+def test_two_streams_with_a_workspace_each_do_not_disturb_each_other():
+    """The head_dim 128 kernels launch one persistent workgroup per CU and hand out their blocks through counters in
+    the workspace: two calls in flight at once, on two streams of the default priority with a workspace each, share the
+    CUs without sharing anything else and give the bits of the same calls run one after the other."""
+    import paper_2509_21275_amd as ca
+    cases = [synth.scaled_case(4, 8), synth.scaled_case(3, 8)]
+    ref, work = [], []
+    for case in cases:
+        q, k, v, do = make_inputs(case)
+        ref.append(run_gpu(case, q, k, v, do))
+        desc = ca.make_desc(case.segs, case.num_q_heads, case.num_kv_heads, case.head_dim, case.total_q, case.total_kv,
+                            case.scale)
+        o = torch.full_like(q, float("nan")); dq = torch.full_like(q, float("nan"))
+        dk = torch.full_like(k, float("nan")); dv = torch.full_like(v, float("nan"))
+        lse = torch.full((case.num_q_heads, case.total_q), float("nan"), dtype=torch.float32, device="cuda")
+        work.append((desc, ca.alloc_workspace(desc), q, k, v, do, o, lse, dq, dk, dv, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for desc, ws, q, k, v, do, o, lse, dq, dk, dv, st in work:
+            ca.chunk_attn_fwd(desc, q, k, v, o, lse, ws, stream=st)
+        for desc, ws, q, k, v, do, o, lse, dq, dk, dv, st in work:
+            ca.chunk_attn_bwd(desc, q, k, v, o, do, lse, dq, dk, dv, 0, ws, stream=st)
+    torch.cuda.synchronize()
+    for (desc, ws, q, k, v, do, o, lse, dq, dk, dv, st), r in zip(work, ref):
+        for x, y in zip((o, lse, dq, dk, dv), r):
+            assert torch.equal(x, y)
