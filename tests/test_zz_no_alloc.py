@@ -77,3 +77,35 @@ def test_static_forward_refuses_what_does_not_fit():
     assert lib.chunk_attn_fwd_static(ctypes.byref(desc), P(q), P(kv), P(kv), P(o), P(lse), None) == ca.TOO_LARGE
     assert "16 MiB" in ca.chunk_attn_strerror(ca.TOO_LARGE)
     torch.cuda.synchronize()
+
+
+def test_static_forward_under_graph_capture():
+    """The callers the entry point is for: captured into a HIP graph (after one eager call, which takes the scratch
+    array's address) and replayed several times with eager work in between, every replay gives the eager bits."""
+    import paper_2509_21275_amd as ca
+    case = synth.ChunkCase("hybrid_big", synth.hybrid_chunk(700, 1500, [300, 129, 64, 1, 257]), 1451, 2951, 8, 2, 128, 71)
+    q, k, v, _ = make_inputs(case)
+    desc = ca.make_desc(case.segs, 8, 2, 128, case.total_q, case.total_kv, case.scale)
+    o_ref = torch.empty_like(q); lse_ref = torch.empty((8, case.total_q), dtype=torch.float32, device="cuda")
+    ca.chunk_attn_fwd_static(desc, q, k, v, o_ref, lse_ref)
+    torch.cuda.synchronize()
+    o = torch.zeros_like(q); lse = torch.zeros_like(lse_ref)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    print("capturing chunk_attn_fwd_static", flush=True)
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            ca.chunk_attn_fwd_static(desc, q, k, v, o, lse, stream=side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        o.fill_(float("nan")); lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref), rep
+        other = synth.ChunkCase("packed_small", synth.packed_chunk([130, 33]), 163, 163, 8, 2, 128, 72)   # eager work
+        q2, k2, v2, _ = make_inputs(other)
+        d2 = ca.make_desc(other.segs, 8, 2, 128, 163, 163, other.scale)
+        ca.chunk_attn_fwd_static(d2, q2, k2, v2, torch.empty_like(q2), torch.empty((8, 163), dtype=torch.float32, device="cuda"))
+        torch.cuda.synchronize()
