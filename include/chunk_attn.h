@@ -206,8 +206,9 @@ int chunk_attn_test_set_bwd_mode(int mode);
 /*
  * Test hook: byte offset, inside the backward workspace of `desc`, of the status word (uint32) of the one-pass
  * backward.  After a head_dim 128 backward in mode 2 has completed it is 0 unless something went wrong: bit 0 = a wave
- * gave up waiting for the workgroup before it in the dQ order (bounded wait; dQ is then wrong), bit 1 = a workgroup
- * ran on another XCD than its index implies (the ordered updates then do not meet in one L2).
+ * gave up waiting for the workgroup before it in the dQ order (bounded wait; dQ is then wrong), bit 1 = an XCD
+ * received more workgroups than the plan has for it (the grid was not dealt to the XCDs round robin; work is then
+ * left undone).
  */
 int chunk_attn_test_bwd_status_offset(const chunk_attn_desc* desc, size_t* offset);
 

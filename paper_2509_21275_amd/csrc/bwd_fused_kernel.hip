@@ -52,7 +52,9 @@ struct FusedParams {
   const int32_t* order;  // item of workgroup b, -1: none
   float* dq_acc;         // [Hq][total_qt32] tiles of 4096 floats
   unsigned* progress;    // [items][4]: stages whose dQ update wave w of the item has completed
-  unsigned* status;      // bit 0: a bounded wait expired; bit 1: a workgroup ran on another XCD than planned; word 32: scratch
+  unsigned* status;      // bit 0: a bounded wait expired; bit 1: an XCD received more workgroups than planned;
+                         // words 8 .. 15: workgroups started per XCD; word 32: scratch
+  int32_t num_slots;     // entries of `order`
   float* sink;           // 64 scratch dQ tiles of 16 KB
   int64_t total_q_tiles, total_qt32;
   int64_t buf_bytes;     // size of one dQ tile array (a chain is split into sub-chains, each with its own array)
@@ -174,17 +176,29 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
   const int role = wave >> 1, pair = wave & 1;
   const int l32 = lane & 31, hh = lane >> 5;
 
-  const int item_id = p.order[blockIdx.x];
+  // The slot of this workgroup in the order: column = the XCD it runs on, row = how many workgroups of that XCD came
+  // before it (a counter per XCD, zero before the launch).  A grid's workgroups are dealt to the XCDs round robin, so
+  // every XCD receives as many workgroups as its column has rows, whichever XCD the first one lands on; taking the
+  // column from the hardware register instead of the workgroup index keeps a chain inside one L2 in any case, and
+  // the predecessor of a slot (an earlier row of the same column) has always started before it.
+  __shared__ int my_slot;
+  if (tid == 0) {
+    const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & 7u;  // XCC_ID
+    const unsigned row = __hip_atomic_fetch_add(p.status + 8 + xcc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int64_t sl = (int64_t)row * kNumXcd + xcc;
+    if (sl >= p.num_slots) atomicOr(p.status, 2u);  // more workgroups on this XCD than its column has rows
+    my_slot = sl < p.num_slots ? (int)sl : -1;
+  }
+  __syncthreads();
+  const int slot = my_slot;
+  if (slot < 0) return;
+  const int item_id = p.order[slot];
   if (item_id < 0) return;
   const FusedItem it = p.items[item_id];
   const int kvh = it.kvh;
   const int G = p.group;
   const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
   const float c = p.scale_log2;
-  {  // the chain's updates meet in one L2 only if the workgroup runs on the XCD its index implies
-    const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & 15u;  // XCC_ID
-    if (xcc != (blockIdx.x & 7u) && tid == 0) atomicOr(p.status, 2u);
-  }
 
   // zero everything but the ring slots the prologue fills
   {
@@ -429,7 +443,7 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
     // tiles left in their head's walk (counting that one)
     const char* const acc_base = reinterpret_cast<const char*>(p.dq_acc);
     // scratch tiles: one of 64, by workgroup index (all workgroups fill their pipelines at the same time when the kernel starts)
-    const char* const sink_tile = reinterpret_cast<const char*>(p.sink) + (blockIdx.x & 63) * 16384 + wave * 4096;
+    const char* const sink_tile = reinterpret_cast<const char*>(p.sink) + (slot & 63) * 16384 + wave * 4096;
     unsigned* const sink_word = p.status + 32;
     int64_t ld_off = acc_tile0, st_off = acc_tile0;
     int ld_left = nqt, st_left = nqt;
@@ -787,6 +801,7 @@ hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const Bw
   p.spin_limit = 1 << 20;
   const int64_t blocks = (int64_t)P.fplan.order.size();
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+  p.num_slots = (int32_t)blocks;
   constexpr int NS = FUSED_DIST + 5;
   const size_t smem = (size_t)2 * NS * 32 * D * 2 + 2 * 4096 * 2 + 2 * 4096 * 2 + 2 * NS * 64 * sizeof(float);
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_fused_pipe_kernel<D>),

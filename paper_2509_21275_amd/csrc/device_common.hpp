@@ -72,7 +72,7 @@ __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
 
 // ---- dynamic assignment of a launch's blocks to persistent workgroups ----
 // A launch has `total` blocks of work (what used to be one workgroup each).  They are dealt to eight queues by index
-// modulo 8: a grid's workgroup b runs on XCD b % 8, so the host's block order already puts blocks that share data
+// modulo 8: a grid's workgroup b normally runs on XCD b % 8, so the host's block order already puts blocks that share data
 // (the same key/value head) on one XCD, whose L2 then serves the stream they share.  One workgroup per CU is launched;
 // it takes blocks from the queue of the XCD it runs on, front to back (the host sorts blocks longest first), and once
 // that queue is empty from the queue with the most blocks left.  The XCDs of a chip do not run at the same speed (their
