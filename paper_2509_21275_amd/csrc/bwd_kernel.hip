@@ -1068,16 +1068,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
           }
         }
         if (m == 2 && ROLE == 0) dma_rows();
-        // Vector work next to the MFMAs.  Role B: pairs 0 .. 7 in mini-steps 4 .. 11 (one half next to each MFMA), pairs
-        // 8 .. 15 two per mini-step after that.  Role A (fma + exponential): one pair next to each MFMA of the second
-        // half of the step; measured against an even spread over the whole step (2.1 % slower), the layout of role B
-        // (0.5 - 1 % slower) and everything in the last four mini-steps (9.6 % slower).
-        if constexpr (ROLE == 0) {
-          if constexpr (m >= 8) vec_pair(std::integral_constant<int, 2 * (m - 8)>{});
-        } else {
-          if constexpr (m >= 4 && m < 12) vec_half(std::integral_constant<int, m - 4>{}, c0);
-          if constexpr (m >= 12) vec_pair(std::integral_constant<int, 8 + 2 * (m - 12)>{});
-        }
+        // Vector work next to the MFMAs: one pair (two scores of a key block) after each MFMA of the second half of the
+        // step; the MFMAs of the first half run unhindered.  Measured for role A (fma + exponential) against an even
+        // spread over the whole step (2.1 % slower), one score per MFMA from mini-step 4 on and two in the last four
+        // mini-steps (0.5 - 1 % slower) and everything in the last four mini-steps (9.6 % slower); for role B against
+        // the second of these (1.2 % slower).
+        if constexpr (m >= 8) vec_pair(std::integral_constant<int, 2 * (m - 8)>{});
         __builtin_amdgcn_sched_barrier(0);
         mma(c1);
         if constexpr (ROLE == 0 && m < 2) {  // (E1)
@@ -1085,12 +1081,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
           r4[2 * m + 1] = lds_asm_read16f<64 * m + 32>(ra);
         }
         if (m >= 3 && m < 3 + 2 * PIECES && ((m - 3) & 1) == 0) dma_piece((m - 3) >> 1);
-        if constexpr (ROLE == 0) {
-          if constexpr (m >= 8) vec_pair(std::integral_constant<int, 2 * (m - 8) + 1>{});
-        } else {
-          if constexpr (m >= 4 && m < 12) vec_half(std::integral_constant<int, m - 4>{}, c1);
-          if constexpr (m >= 12) vec_pair(std::integral_constant<int, 9 + 2 * (m - 12)>{});
-        }
+        if constexpr (m >= 8) vec_pair(std::integral_constant<int, 2 * (m - 8) + 1>{});
         if constexpr (m == 14) {  // bookkeeping for the next step (the copies of this step have been issued)
           dma_advance();
           sA = sA == NS - 1 ? 0 : sA + 1;
