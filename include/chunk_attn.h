@@ -195,6 +195,14 @@ int chunk_attn_test_set_fwd_rescale_limit(float log2_growth);
 int chunk_attn_measure_mfma_rate(int milliseconds, void* scratch, size_t scratch_bytes, void* stream, double* tflops);
 
 /*
+ * The same measurement with `workgroups` workgroups (1 .. number of CUs) instead of one per CU, i.e. with only part
+ * of the chip busy: the rate per busy CU rises as fewer are busy, which shows that the sustained matrix rate of the
+ * whole chip is set by its power budget and not by a fixed clock.  CHUNK_ATTN_INVALID_ARG for a count out of range.
+ */
+int chunk_attn_measure_mfma_rate_on(int milliseconds, int workgroups, void* scratch, size_t scratch_bytes, void* stream,
+                                    double* tflops);
+
+/*
  * Test and measurement hook: which backward chunk_attn_bwd / chunk_attn_bwd_f32kv run for head_dim 128.
  * 0: the library's choice; 1: two kernels (dQ query-stationary, dK/dV key-stationary, P recomputed in both);
  * 2: one pass (the key-stationary kernel also forms dQ and adds it into float32 tiles in the workspace in a fixed

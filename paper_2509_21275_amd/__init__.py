@@ -215,6 +215,18 @@ def chunk_attn_measure_mfma_rate(milliseconds: int = 500, stream=None) -> float:
     return out.value
 
 
+def chunk_attn_measure_mfma_rate_on(workgroups: int, milliseconds: int = 500, stream=None) -> float:
+    """The same with `workgroups` workgroups instead of one per CU (part of the chip busy)."""
+    import torch
+    scratch = torch.empty(1052672, dtype=torch.uint8, device="cuda")
+    out = ctypes.c_double(0.0)
+    rc = _lib.chunk_attn_measure_mfma_rate_on(ctypes.c_int(milliseconds), ctypes.c_int(workgroups), _ptr(scratch),
+                                              ctypes.c_size_t(scratch.numel()), _stream(stream), ctypes.byref(out))
+    if rc != 0:
+        raise ChunkAttnError(rc)
+    return out.value
+
+
 def chunk_attn_test_set_bwd_mode(mode: int) -> None:
     """Test hook: 0 = library's choice, 1 = two-kernel backward, 2 = one-pass backward (head_dim 128)."""
     rc = _lib.chunk_attn_test_set_bwd_mode(ctypes.c_int(mode))

@@ -49,8 +49,24 @@ __global__ __launch_bounds__(256) void fill_operands_kernel(unsigned short* dst,
 }  // namespace
 }  // namespace chunk_attn
 
+namespace {
+int measure_mfma_rate(int milliseconds, int workgroups, void* scratch, size_t scratch_bytes, void* stream_v, double* tflops);
+}
+
 extern "C" int chunk_attn_measure_mfma_rate(int milliseconds, void* scratch, size_t scratch_bytes, void* stream_v,
                                             double* tflops) {
+  return measure_mfma_rate(milliseconds, 0, scratch, scratch_bytes, stream_v, tflops);
+}
+
+extern "C" int chunk_attn_measure_mfma_rate_on(int milliseconds, int workgroups, void* scratch, size_t scratch_bytes,
+                                               void* stream_v, double* tflops) {
+  if (workgroups < 1) return CHUNK_ATTN_INVALID_ARG;
+  return measure_mfma_rate(milliseconds, workgroups, scratch, scratch_bytes, stream_v, tflops);
+}
+
+namespace {
+// workgroups == 0: one per CU
+int measure_mfma_rate(int milliseconds, int workgroups, void* scratch, size_t scratch_bytes, void* stream_v, double* tflops) {
   using namespace chunk_attn;
   constexpr size_t kNeed = 4096 + 1024 * 256 * sizeof(float);   // operands, then one float per thread of up to 1024 workgroups
   if (!scratch || !tflops || milliseconds < 1 || milliseconds > 10000) return CHUNK_ATTN_INVALID_ARG;
@@ -60,6 +76,8 @@ extern "C" int chunk_attn_measure_mfma_rate(int milliseconds, void* scratch, siz
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
     return CHUNK_ATTN_HIP_ERROR;
   if (cus < 1 || cus > 1024) return CHUNK_ATTN_HIP_ERROR;
+  if (workgroups > cus) return CHUNK_ATTN_INVALID_ARG;
+  if (workgroups > 0) cus = workgroups;  // from here on: the number of workgroups launched
   unsigned short* src = static_cast<unsigned short*>(scratch);
   float* out = reinterpret_cast<float*>(static_cast<char*>(scratch) + 4096);
   hipLaunchKernelGGL(fill_operands_kernel, dim3(8), dim3(256), 0, stream, src, 2048);
@@ -88,3 +106,4 @@ extern "C" int chunk_attn_measure_mfma_rate(int milliseconds, void* scratch, siz
   if (rc == CHUNK_ATTN_OK) *tflops = best;
   return rc;
 }
+}  // namespace
