@@ -62,6 +62,23 @@ std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, int width, std
   return jobs;
 }
 
+// Order of the query-stationary work items: sequence by sequence, the sequence with the most keys first, and inside a
+// sequence the query tile that walks the most keys first.  The workgroups of an XCD then work on neighbouring tiles of
+// one sequence and share its K / V stream in the L2, the long sequences still start first, and every sequence ends in
+// short items that fill the tail (the workgroups balance the rest by taking blocks from each other's queues).
+// Measured against "longest walk first over the whole chunk": +1.7 % on the packed 64K chunk, nothing on the others.
+template <class Item>
+static void by_sequence_then_walk(const chunk_attn_desc* d, std::vector<Item>& items) {
+  std::vector<int32_t> keys_of(d->total_kv + 1, 0);  // by the first key row of a segment: its number of keys
+  for (int t = 0; t < d->num_segments; ++t) keys_of[d->segments[t].kv_start] = d->segments[t].kv_len;
+  std::stable_sort(items.begin(), items.end(), [&](const Item& a, const Item& b) {
+    const int32_t ka = keys_of[a.kv_row0], kb = keys_of[b.kv_row0];
+    if (ka != kb) return ka > kb;
+    if (a.kv_row0 != b.kv_row0) return a.kv_row0 < b.kv_row0;
+    return (int64_t)a.n0 + a.q_rows > (int64_t)b.n0 + b.q_rows;
+  });
+}
+
 std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows) {
   std::vector<FwdItem> items;
   int32_t kv_tile0 = 0;
@@ -79,10 +96,7 @@ std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows) {
     }
     kv_tile0 += (s.kv_len + 63) / 64;
   }
-  // most keys first, so the long items start early and the short ones fill the tail
-  std::stable_sort(items.begin(), items.end(), [](const FwdItem& a, const FwdItem& b) {
-    return (int64_t)a.n0 + a.q_rows > (int64_t)b.n0 + b.q_rows;
-  });
+  by_sequence_then_walk(d, items);
   return items;
 }
 
@@ -105,9 +119,7 @@ std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows) {
     kv_tile0 += (s.kv_len + 31) / 32;
     q_tile0 += (s.q_len + 63) / 64;
   }
-  std::stable_sort(items.begin(), items.end(), [](const DqItem& a, const DqItem& b) {
-    return (int64_t)a.n0 + a.q_rows > (int64_t)b.n0 + b.q_rows;
-  });
+  by_sequence_then_walk(d, items);
   return items;
 }
 
@@ -133,9 +145,9 @@ std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys) {
     }
     q_tile0 += (s.q_len + 63) / 64;
   }
-  std::stable_sort(items.begin(), items.end(), [](const DkvItem& a, const DkvItem& b) {
-    return a.n_qt - a.qt_first > b.n_qt - b.qt_first;
-  });
+  // sequence by sequence, longest first; the key blocks of a sequence in key order, which is longest walk first (see
+  // by_sequence_then_walk)
+  std::stable_sort(items.begin(), items.end(), [](const DkvItem& a, const DkvItem& b) { return a.n_qt > b.n_qt; });
   return items;
 }
 
