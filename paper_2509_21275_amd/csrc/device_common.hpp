@@ -74,7 +74,7 @@ __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
 // A launch has `total` blocks of work (what used to be one workgroup each).  They are dealt to eight queues by index
 // modulo 8: a grid's workgroup b normally runs on XCD b % 8, so the host's block order already puts blocks that share data
 // (the same key/value head) on one XCD, whose L2 then serves the stream they share.  One workgroup per CU is launched;
-// it takes blocks from the queue of the XCD it runs on, front to back (the host sorts blocks longest first), and once
+// it takes blocks from the queue of the XCD it runs on, front to back (the host puts long sequences first and ends every sequence with its short blocks), and once
 // that queue is empty from the queue with the most blocks left.  The XCDs of a chip do not run at the same speed (their
 // finishing times differed by 4 - 7 % with a fixed share each); this way the fast ones take over what the slow ones
 // have not started, and only the blocks taken over lose their L2 neighbourhood.  `taken` (device, 8 counters, zero when
