@@ -224,6 +224,29 @@ def main():
     torch.cuda.synchronize()
     call_ms = {(i, kind): evpool.elapsed_ms(*ev) for i, kind, ev in call_ev}
 
+    # the clock the three main kernels run at: one more step with the library's clock log switched on, every call read
+    # back by itself (include/chunk_attn.h: chunk_attn_measure_set_clock_log); shader clocks / 100 MHz ticks, summed over
+    # the workgroups of all calls
+    clock_buf = torch.zeros(ca.CLOCK_LOG_BYTES // 8, dtype=torch.int64, device=dev)
+    clock_sum = {k: [0, 0] for k in ca.CLOCK_LOG_KERNELS}
+    ca.chunk_attn_measure_set_clock_log(clock_buf)
+    try:
+        for order, kind in ((fwd_order, "fwd"), (bwd_order, "bwd")):
+            for i in order:
+                c = calls[i]
+                clock_buf.zero_()
+                if kind == "fwd":
+                    ca.chunk_attn_fwd(c["desc"], c["q"], c["k"], c["v"], c["o"], c["lse"], c["ws"])
+                else:
+                    ca.chunk_attn_bwd(c["desc"], c["q"], c["k"], c["v"], c["o"], c["do"], c["lse"], c["dq"], c["dk"], c["dv"],
+                                      c["accumulate"], c["ws"])
+                torch.cuda.synchronize()
+                for k, v in ca.clock_log_sums(clock_buf).items():
+                    clock_sum[k][0] += v["shader_clocks"]; clock_sum[k][1] += v["ticks_100mhz"]
+    finally:
+        ca.chunk_attn_measure_set_clock_log(None)
+    kernel_clock_mhz = {k: round(100.0 * v[0] / v[1], 1) if v[1] else None for k, v in clock_sum.items()}
+
     # per-kernel durations from the HIP events recorded on the launch stream
     per_call = []
     fwd_k_ms = bwd_k_ms = 0.0
@@ -279,6 +302,9 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "measured_clock_peak": round(measured_peak, 1),
                      "frac_of_measured_clock_peak": round(achieved / measured_peak, 4),
+                     "kernel_clock_mhz": kernel_clock_mhz,
+                     "frac_of_peak_at_kernel_clock": (round(achieved / (PEAK_BF16_TFLOPS * kernel_clock_mhz["dkv"] / 2400.0), 4)
+                                                      if kernel_clock_mhz["dkv"] else None),
                      "traffic": recorded_traffic(), "launches_per_step": n_launch,
                      "avg_launch_ms": round(bwd_k_ms / n_launch, 4),
                      "flops_per_launch_avg": dkv_flops / n_launch,

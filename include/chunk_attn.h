@@ -203,6 +203,20 @@ int chunk_attn_measure_mfma_rate_on(int milliseconds, int workgroups, void* scra
                                     double* tflops);
 
 /*
+ * Measurement hook (not part of the method): the clock the three pipelined kernels (forward, dQ, dK/dV; head_dim 64,
+ * 96 and 128) actually run at.  `device_buffer`: DEVICE memory, 8-byte aligned, at least CHUNK_ATTN_CLOCK_LOG_BYTES
+ * (else CHUNK_ATTN_WORKSPACE_TOO_SMALL; CHUNK_ATTN_INVALID_ARG if misaligned), owned by the caller and kept alive until
+ * the hook is switched off with a null pointer.  While it is set, every workgroup of those kernels writes four 64-bit
+ * values when it starts and when it has run out of work: section k of the buffer (k = 0 forward, 1 dQ, 2 dK/dV; 4096
+ * values each) holds, for workgroup b < 1024, at [4 b .. 4 b + 3] = {constant 100 MHz counter at the start, at the
+ * end, shader-clock counter at the start, at the end}.  The ratio of the differences, times 100 MHz, is the clock.
+ * Each launch overwrites its kernel's section; clear the buffer before a launch to tell entries apart.  Process-wide;
+ * the kernels' results do not depend on it.
+ */
+#define CHUNK_ATTN_CLOCK_LOG_BYTES (3 * 4096 * 8)
+int chunk_attn_measure_set_clock_log(void* device_buffer, size_t bytes);
+
+/*
  * Test and measurement hook: which backward chunk_attn_bwd / chunk_attn_bwd_f32kv run for head_dim 128.
  * 0: the library's choice; 1: two kernels (dQ query-stationary, dK/dV key-stationary, P recomputed in both);
  * 2: one pass (the key-stationary kernel also forms dQ and adds it into float32 tiles in the workspace in a fixed

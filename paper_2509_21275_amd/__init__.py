@@ -60,6 +60,8 @@ def _load():
     lib.chunk_attn_bwd_f32kv.restype = ctypes.c_int
     lib.chunk_attn_profile_events.argtypes = [vp, vp]
     lib.chunk_attn_profile_events.restype = ctypes.c_int
+    lib.chunk_attn_measure_set_clock_log.argtypes = [vp, sz]
+    lib.chunk_attn_measure_set_clock_log.restype = ctypes.c_int
     return lib
 
 
@@ -225,6 +227,34 @@ def chunk_attn_measure_mfma_rate_on(workgroups: int, milliseconds: int = 500, st
     if rc != 0:
         raise ChunkAttnError(rc)
     return out.value
+
+
+CLOCK_LOG_BYTES = 3 * 4096 * 8
+CLOCK_LOG_KERNELS = ("fwd", "dq", "dkv")
+
+
+def chunk_attn_measure_set_clock_log(buffer) -> None:
+    """Measurement hook: while `buffer` (a CUDA tensor of at least CLOCK_LOG_BYTES bytes, kept alive by the caller) is
+    set, the workgroups of the pipelined forward, dQ and dK/dV kernels log their start and end counters there; None
+    switches it off."""
+    if buffer is None:
+        rc = _lib.chunk_attn_measure_set_clock_log(None, 0)
+    else:
+        rc = _lib.chunk_attn_measure_set_clock_log(_ptr(buffer), ctypes.c_size_t(buffer.numel() * buffer.element_size()))
+    if rc != 0:
+        raise ChunkAttnError(rc)
+
+
+def clock_log_sums(buffer) -> dict:
+    """Decodes a clock log (after a synchronisation): per kernel {"workgroups", "ticks_100mhz", "shader_clocks"}, the
+    last two summed over the workgroups that logged both a start and an end."""
+    log = buffer.view(-1).cpu().numpy().view("uint64")[:3 * 4096].reshape(3, 1024, 4).astype("int64")
+    out = {}
+    for name, sec in zip(CLOCK_LOG_KERNELS, log):
+        ok = (sec[:, 0] > 0) & (sec[:, 1] > sec[:, 0]) & (sec[:, 3] > sec[:, 2])
+        out[name] = {"workgroups": int(ok.sum()), "ticks_100mhz": int((sec[ok, 1] - sec[ok, 0]).sum()),
+                     "shader_clocks": int((sec[ok, 3] - sec[ok, 2]).sum())}
+    return out
 
 
 def chunk_attn_test_set_bwd_mode(mode: int) -> None:

@@ -128,6 +128,7 @@ StagingRing g_ring;
 std::atomic<float> g_fwd_rescale_limit{60.0f};
 
 std::atomic<int> g_bwd_mode{0};
+std::atomic<unsigned long long*> g_clock_log{nullptr};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
@@ -326,6 +327,10 @@ NarrowBwdLayout narrow_bwd_layout(const chunk_attn_desc* d, size_t inner_bytes) 
 
 namespace chunk_attn {
 int bwd_mode() { return g_bwd_mode.load(); }
+unsigned long long* clock_log(int which) {
+  unsigned long long* base = g_clock_log.load();
+  return base ? base + (size_t)which * kClockLogEntries : nullptr;
+}
 ProfileEvents& profile_events() {
   static thread_local ProfileEvents ev;
   return ev;
@@ -350,6 +355,17 @@ int chunk_attn_shutdown(void) {
 int chunk_attn_test_set_bwd_mode(int mode) {
   if (mode < 0 || mode > 2) return CHUNK_ATTN_INVALID_ARG;
   g_bwd_mode.store(mode);
+  return CHUNK_ATTN_OK;
+}
+
+int chunk_attn_measure_set_clock_log(void* device_buffer, size_t bytes) {
+  if (device_buffer == nullptr) {
+    g_clock_log.store(nullptr);
+    return CHUNK_ATTN_OK;
+  }
+  if ((reinterpret_cast<uintptr_t>(device_buffer) & 7) != 0) return CHUNK_ATTN_INVALID_ARG;
+  if (bytes < 3 * kClockLogEntries * sizeof(unsigned long long)) return CHUNK_ATTN_WORKSPACE_TOO_SMALL;
+  g_clock_log.store(static_cast<unsigned long long*>(device_buffer));
   return CHUNK_ATTN_OK;
 }
 
@@ -471,6 +487,7 @@ int chunk_attn_fwd(const chunk_attn_desc* desc, const void* q, const void* k, co
   p.redo = desc->head_dim == 128 ? reinterpret_cast<int32_t*>(ws + L.flags_off) : nullptr;
   p.any_redo = reinterpret_cast<int32_t*>(ws + L.flags_off) + L.blocks;
   p.taken = p.any_redo + 1;
+  p.clock_log = clock_log(0);
   p.ref_limit = g_fwd_rescale_limit.load();
   const int64_t blocks = L.blocks;
   if (blocks > 0x7fffffff) return CHUNK_ATTN_UNSUPPORTED;
@@ -541,6 +558,7 @@ int chunk_attn_fwd_static(const chunk_attn_desc* desc, const void* q, const void
   p.redo = desc->head_dim == 128 ? reinterpret_cast<int32_t*>(ws + L.flags_off) : nullptr;
   p.any_redo = reinterpret_cast<int32_t*>(ws + L.flags_off) + L.blocks;
   p.taken = p.any_redo + 1;
+  p.clock_log = clock_log(0);
   p.ref_limit = g_fwd_rescale_limit.load();
   e = launch_fwd(p, desc->head_dim, (int)L.blocks, reinterpret_cast<const TileJob*>(ws + L.jobs_off), (int)L.kv_tiles, stream);
   if (e != hipSuccess) return hip_fail(e, "forward launch");

@@ -91,6 +91,7 @@ struct DqParams {
   int32_t num_q_heads, num_kv_heads, group, heads_per_wg, head_splits;
   float scale, scale_log2;
   int32_t* taken;        // 8 block-queue counters of the pipelined kernel (zero before the launch)
+  unsigned long long* clock_log;  // null, or where the pipelined kernel's workgroups log their clocks
 };
 
 template <int D, int WAVES>
@@ -327,6 +328,7 @@ struct DkvParams {
   int32_t accumulate;
   int32_t out_f32;      // dk / dv point to fp32 arrays of the same shape
   int32_t* taken;       // 8 block-queue counters of the pipelined kernel (zero before the launch)
+  unsigned long long* clock_log;  // null, or where the pipelined kernel's workgroups log their clocks
 };
 
 // Four consecutive elements of a dK / dV row: stored, or added to what is there, as bf16 or as fp32.
@@ -743,6 +745,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   // before it is known which workgroup is free first).
   __shared__ int next_block;
   const int xcd = xcd_of_this_wave();
+  clock_log_stamp(p.clock_log, 0);
   int blk = 0;
   if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
   blk = broadcast_from_wave0(&next_block, blk);
@@ -1143,6 +1146,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
   blk = broadcast_from_wave0(&next_block, nb);
   }
+  clock_log_stamp(p.clock_log, 1);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1196,6 +1200,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
   // enough for the answer to arrive by the time it is needed, and not earlier (that would fix the order of the blocks
   // before it is known which workgroup is free first).
   const int xcd = xcd_of_this_wave();
+  clock_log_stamp(p.clock_log, 0);
   int blk = 0;
   if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
   blk = broadcast_from_wave0(next_block, blk);
@@ -1522,6 +1527,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
   if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
   blk = broadcast_from_wave0(next_block, nb);
   }
+  clock_log_stamp(p.clock_log, 1);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1588,6 +1594,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.heads_per_wg = heads_per_wg(group, dq_waves(D)); p.head_splits = group / p.heads_per_wg;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
     p.taken = reinterpret_cast<int32_t*>(ws + P.queues_off);
+    p.clock_log = clock_log(1);
     const int64_t blocks = (int64_t)P.dq_items.size() * d->num_kv_heads * p.head_splits;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if constexpr (D == 128) {
@@ -1616,6 +1623,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     p.accumulate = a.accumulate ? 1 : 0;
     p.out_f32 = a.dkv_f32 ? 1 : 0;
     p.taken = reinterpret_cast<int32_t*>(ws + P.queues_off) + kBlockQueues;
+    p.clock_log = clock_log(2);
     static_assert(DKV_KEYS == 128, "the head_dim 64 and 128 kernels cover 128 keys per workgroup");
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;

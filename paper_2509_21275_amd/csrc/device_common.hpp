@@ -70,6 +70,20 @@ __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
 }
 
+// ---- clock log of a persistent workgroup (measurement only) ----
+// When the caller of the library has asked for it, the first lane of every persistent workgroup records two counters
+// when it starts (`end` = 0) and when it has run out of blocks (`end` = 1): the constant 100 MHz counter and the
+// shader-clock counter.  The ratio of the two differences is the clock the kernel ran at.  Entry of workgroup b:
+// {100 MHz start, 100 MHz end, shader clock start, shader clock end}.  Grids beyond kClockLogWorkgroups are not logged.
+constexpr int kClockLogWorkgroups = 1024;
+__device__ __forceinline__ void clock_log_stamp(unsigned long long* log, int end) {
+  if (log != nullptr && threadIdx.x == 0 && blockIdx.x < kClockLogWorkgroups) {
+    unsigned long long* e = log + 4 * blockIdx.x + end;
+    e[0] = __builtin_amdgcn_s_memrealtime();
+    e[2] = __builtin_amdgcn_s_memtime();
+  }
+}
+
 // ---- dynamic assignment of a launch's blocks to persistent workgroups ----
 // A launch has `total` blocks of work (what used to be one workgroup each).  They are dealt to eight queues by index
 // modulo 8: a grid's workgroup b normally runs on XCD b % 8, so the host's block order already puts blocks that share data

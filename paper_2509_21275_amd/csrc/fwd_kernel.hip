@@ -321,6 +321,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
   // enough for the answer to arrive by the time it is needed, and not earlier (that would fix the order of the blocks
   // before it is known which workgroup is free first).
   const int xcd = xcd_of_this_wave();
+  clock_log_stamp(p.clock_log, 0);
   int blk = 0;
   if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
   blk = broadcast_from_wave0(next_block, blk);
@@ -662,6 +663,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
   if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
   blk = broadcast_from_wave0(next_block, nb);
   }
+  clock_log_stamp(p.clock_log, 1);
 }
 
 // The dynamic-LDS limit of a kernel is raised once per process (thread-safe: a function-local static).

@@ -31,6 +31,7 @@ struct FwdParams {
   int32_t* any_redo;                         // raised together with any redo flag (gates the second pass's preparation)
   float ref_limit;                           // log2 growth of the row maximum past the first tile's that raises the flag
   int32_t* taken;                            // 8 block-queue counters of the pipelined forward (zero before the launch)
+  unsigned long long* clock_log;             // null, or where the pipelined forward's workgroups log their clocks
 };
 
 // rows of query tile per forward work item for a given head layout
@@ -99,6 +100,10 @@ constexpr int kNumXcd = 8;  // XCDs of an MI355X: workgroup b runs on XCD b % 8
 
 // 0: the library's choice, 1: the two-kernel backward, 2: the one-pass backward (head_dim 128 only)
 int bwd_mode();
+// Device memory the caller has set aside for the clock logs of the three pipelined kernels (null: none), and the section
+// of kernel `which` in it (0 forward, 1 dQ, 2 dK/dV), kClockLogEntries values of 8 bytes each.
+constexpr size_t kClockLogEntries = 4 * 1024;
+unsigned long long* clock_log(int which);
 hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& plan, const float* lse2p, const float* dsp,
                             hipStream_t stream);
 // Fills the offsets (and, if with_plan, the schedules) for a validated descriptor.

@@ -177,3 +177,33 @@ def test_two_streams_with_a_workspace_each_do_not_disturb_each_other():
     for (desc, ws, q, k, v, do, o, lse, dq, dk, dv, st), r in zip(work, ref):
         for x, y in zip((o, lse, dq, dk, dv), r):
             assert torch.equal(x, y)
+
+
+def test_clock_log_reports_a_plausible_clock_and_changes_no_result():
+    """The measurement hook: with the log switched on the three pipelined kernels give the same bits, every workgroup
+    leaves a start and an end, and the clock they imply lies between 0.5 and 2.6 GHz (the chip's peak is 2.4)."""
+    import paper_2509_21275_amd as ca
+    case = synth.scaled_case(4, 8)
+    q, k, v, do = make_inputs(case)
+    ref = run_gpu(case, q, k, v, do)
+    buf = torch.zeros(ca.CLOCK_LOG_BYTES // 8, dtype=torch.int64, device="cuda")
+    ca.chunk_attn_measure_set_clock_log(buf)
+    try:
+        got = run_gpu(case, q, k, v, do)
+        torch.cuda.synchronize()
+    finally:
+        ca.chunk_attn_measure_set_clock_log(None)
+    for x, y in zip(ref, got):
+        assert torch.equal(x, y)
+    sums = ca.clock_log_sums(buf)
+    print(sums, flush=True)
+    for name in ca.CLOCK_LOG_KERNELS:
+        s = sums[name]
+        assert 1 <= s["workgroups"] <= 1024
+        mhz = 100.0 * s["shader_clocks"] / s["ticks_100mhz"]
+        assert 500.0 < mhz < 2600.0, (name, mhz)
+    # switched off again: a later call leaves the buffer alone
+    buf.zero_()
+    run_gpu(case, q, k, v, do)
+    torch.cuda.synchronize()
+    assert int(buf.abs().sum()) == 0

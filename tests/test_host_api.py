@@ -107,6 +107,19 @@ def test_null_descriptor_and_messages(ca):
         assert isinstance(ca.chunk_attn_strerror(code), str) and ca.chunk_attn_strerror(code)
 
 
+def test_clock_log_hook_checks_its_buffer(ca):
+    """The hook only stores the pointer: size and alignment are checked on the host, null switches it off."""
+    import ctypes
+    lib = ctypes.CDLL(ca.LIB_PATH)
+    lib.chunk_attn_measure_set_clock_log.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    lib.chunk_attn_measure_set_clock_log.restype = ctypes.c_int
+    assert ca.CLOCK_LOG_BYTES == 3 * 4096 * 8
+    assert lib.chunk_attn_measure_set_clock_log(None, 0) == ca.OK
+    assert lib.chunk_attn_measure_set_clock_log(ctypes.c_void_p(4096), ca.CLOCK_LOG_BYTES - 1) == ca.WORKSPACE_TOO_SMALL
+    assert lib.chunk_attn_measure_set_clock_log(ctypes.c_void_p(4100), ca.CLOCK_LOG_BYTES) == ca.INVALID_ARG
+    assert lib.chunk_attn_measure_set_clock_log(None, 0) == ca.OK
+
+
 def test_shutdown_without_any_upload_is_a_no_op(ca):
     # nothing has been uploaded in this process: there is nothing to release, and no GPU call is made
     lib = ctypes.CDLL(ca.LIB_PATH)
