@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
   }
 
   const int nqt = it.n_qt - it.qt_first;
-  const int n_iter = nqt * G;  // stages: (head in group, query tile), head-major
+  const int n_iter = nqt * G;  // stages: (query tile, head in group), the heads of a tile one after the other
 
   // ---- staging of Q / dO / LSE / D, as in bwd_dkv_pipe_kernel ----
   unsigned v_full[PER], v_last[PER];
@@ -232,31 +232,32 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
   const char* d_q = reinterpret_cast<const char*>(p.q + roff0);
   const char* d_g = reinterpret_cast<const char*>(p.d_o + roff0);
   const char* d_r = reinterpret_cast<const char*>(((wave & 1) ? p.dsp : p.lse2p) + rv0g);
-  const int64_t tile_bytes = (int64_t)BM * q_stride * 2;
-  const int64_t head_bytes = (int64_t)D * 2 - (nqt - 1) * tile_bytes;
-  const int64_t head_rows_bytes = (p.total_q_tiles * 64 - (int64_t)(nqt - 1) * BM) * 4;
-  int d_left = nqt, d_heads = G;
+  const int64_t head_bytes = (int64_t)D * 2;                             // to the next head of the group, same tile
+  const int64_t head_rows_bytes = p.total_q_tiles * 64 * 4;
+  const int64_t tile_bytes = (int64_t)BM * q_stride * 2 - (G - 1) * head_bytes;   // from the last head to the first, next tile
+  const int64_t tile_rows_bytes = (int64_t)BM * 4 - (G - 1) * head_rows_bytes;
+  int d_heads = G, d_tiles = nqt;
   unsigned d_slot = 0;
   const unsigned lane4 = (unsigned)lane * 4u;
   lds_f32* const rows_dst = (wave & 1) ? dsum_s : lse_s;
   auto dma_rows = [&]() __attribute__((always_inline)) { dma4(d_r + lane4, rows_dst + d_slot / (QT / RV)); };
   auto dma_piece = [&](int i) __attribute__((always_inline)) {
     const int piece = i * NW + wave;
-    const unsigned voff = d_left == 1 ? v_last[i] : v_full[i];
+    const unsigned voff = d_tiles == 1 ? v_last[i] : v_full[i];
     const char* base = i < NP / NW ? d_q : d_g;
     lds_bf16* dst = L + (i < NP / NW ? Q_OFF + piece * 512 : G_OFF + (piece - NP) * 512) + d_slot;
     dma16(base + voff, dst);
   };
   auto dma_advance = [&]() __attribute__((always_inline)) {
-    if (__builtin_expect(d_left > 1, 1)) {
-      --d_left;
-      d_q += tile_bytes; d_g += tile_bytes; d_r += BM * 4;
-    } else {
-      const bool more = d_heads > 1;
-      d_heads -= more ? 1 : 0;
-      d_left = more ? nqt : 1;
-      const int64_t hb = more ? head_bytes : 0, hr = more ? head_rows_bytes : 0;
-      d_q += hb; d_g += hb; d_r += hr;
+    if (d_heads > 1) {
+      --d_heads;
+      d_q += head_bytes; d_g += head_bytes; d_r += head_rows_bytes;
+    } else {  // on to the next query tile; after the last stage, stay on it
+      const bool more = d_tiles > 1;
+      d_tiles -= more ? 1 : 0;
+      d_heads = more ? G : 1;
+      const int64_t tb = more ? tile_bytes : 0, tr = more ? tile_rows_bytes : 0;
+      d_q += tb; d_g += tb; d_r += tr;
     }
     d_slot = d_slot == (unsigned)((NS - 1) * QT) ? 0u : d_slot + (unsigned)QT;
   };
@@ -322,7 +323,8 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
   // tile of a stage: ((kvh G + head in group) total_qt32 + dq_tile0 + query tile) x 16 KB, this wave's 4 KB of it, 16 bytes per
   // lane per register group (4 groups, 1 KB apart)
   const int64_t acc_tile0 = it.buf * p.buf_bytes + ((int64_t)(kvh * G) * p.total_qt32 + it.dq_tile0 + it.qt_first) * 16384 + wave * 4096;
-  const int64_t acc_head_bytes = (p.total_qt32 - (nqt - 1)) * 16384;  // from a head's last tile to the next head's first
+  const int64_t acc_head_bytes = p.total_qt32 * 16384;                    // to the same tile of the next head
+  const int64_t acc_tile_bytes = 16384 - (G - 1) * acc_head_bytes;        // from the last head to the first, next tile
   const unsigned lane16 = (unsigned)lane * 16u;
 
   auto body = [&](auto role_c) __attribute__((always_inline)) {
@@ -376,6 +378,7 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
 
     int sA = ROLE ? NS - 2 : 0;
     int s_qt = it.qt_first;
+    int s_heads = G;
     f32x16 mask_c[2] = {zero16, zero16};
     bool mask_set = false;
     f32x16 x[2][2];
@@ -440,14 +443,15 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) dq_old[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     // running tile pointers (bytes into dq_acc) of the stage to load (ld_) and of the stage to store (st_), with the
-    // tiles left in their head's walk (counting that one)
+    // heads left in their query tile (counting that one)
     const char* const acc_base = reinterpret_cast<const char*>(p.dq_acc);
     // scratch tiles: one of 64, by workgroup index (all workgroups fill their pipelines at the same time when the kernel starts)
     const char* const sink_tile = reinterpret_cast<const char*>(p.sink) + (slot & 63) * 16384 + wave * 4096;
     unsigned* const sink_word = p.status + 32;
     int64_t ld_off = acc_tile0, st_off = acc_tile0;
-    int ld_left = nqt, st_left = nqt;
-    unsigned need = (unsigned)it.delta_qt + 1u;   // predecessor's progress required before the next load
+    int ld_left = G, st_left = G;                  // heads left in the tile of the stage to load / to store
+    // predecessor's progress required before the next load: its walk begins delta_qt tiles (of G stages) before this one
+    unsigned need = (unsigned)(it.delta_qt * G) + 1u;
     bool dead = !has_pred;                         // no more waiting: no predecessor, or a wait expired
 
     auto step = [&](int g, f32x16 (&cur)[2], f32x16 (&nxt)[2], bf16x8 (&f_old)[2][2],
@@ -538,8 +542,8 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
             st_v[0] += dq_old[0]; st_v[1] += dq_old[1]; st_v[2] += dq_old[2]; st_v[3] += dq_old[3];
           }
           if (do_store) {
-            if (st_left > 1) { --st_left; st_off += 16384; }
-            else { st_left = nqt; st_off += acc_head_bytes; }
+            if (st_left > 1) { --st_left; st_off += acc_head_bytes; }
+            else { st_left = G; st_off += acc_tile_bytes; }
           }
         }
         if constexpr (k >= 0 && k < 4) {   // tile stores
@@ -568,8 +572,9 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
           }
           ld_p = acc_base + (in_load ? ld_off : acc_tile0);
           if (in_load) {
-            if (ld_left > 1) { --ld_left; ld_off += 16384; need += 1u; }
-            else { ld_left = nqt; ld_off += acc_head_bytes; need += 1u + (unsigned)it.delta_qt; }
+            need += 1u;
+            if (ld_left > 1) { --ld_left; ld_off += acc_head_bytes; }
+            else { ld_left = G; ld_off += acc_tile_bytes; }
           }
         }
         if constexpr (k >= 4 && k < 8) {   // tile loads
@@ -683,7 +688,10 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
         if constexpr (m == 22) {  // after the step's last operand copy
           dma_advance();
           sA = sA == NS - 1 ? 0 : sA + 1;
-          if (ROLE == 0 && ++s_qt == it.n_qt) s_qt = it.qt_first;
+          if (ROLE == 0 && --s_heads == 0) {
+            s_heads = G;
+            ++s_qt;
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
         }

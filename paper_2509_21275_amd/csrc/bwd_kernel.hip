@@ -770,7 +770,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   }
 
   const int nqt = it.n_qt - it.qt_first;
-  const int n_iter = nqt * G;  // stages: (head in group, query tile), head-major
+  // stages: (query tile, head in group), the heads of a tile one after the other, the tiles upwards from the first one
+  // that sees the block's keys or (it.reverse, the host's choice) downwards from the segment's last one.  Workgroups that walk the same rows at
+  // about the same time (the key blocks of one key/value head run on one XCD) then touch, per query row, one run of
+  // G x D contiguous elements, and blocks of different walk lengths stay side by side for the whole of their common
+  // part instead of drifting apart head by head.
+  const int n_iter = nqt * G;
 
   // ---- staging: copy i of a role A wave is piece `pair` of Q (i = 0) or of dO (i = 1), the first of the two waves
   // also copies the stage's LSE rows, the second its D rows; copy i of a role B wave is piece 2 + 2 (i % 3) + pair of Q
@@ -793,36 +798,40 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   // Wave-uniform state of the copies, kept as running byte pointers so that a step spends only a handful of scalar
   // instructions on it: the first row of the next stage to copy in Q and in dO, its LSE / D rows, the stages left in
   // the current head's walk (counting that one), the heads left (counting the current one), the ring slot.
-  const int64_t roff0 = (int64_t)(it.q_row_seg + it.qt_first * BM) * q_stride + (int64_t)(kvh * G) * D;
-  const int64_t rv0 = ((int64_t)(kvh * G) * p.total_q_tiles + it.q_tile0) * 64 + it.qt_first * BM;
+  const bool down = it.reverse != 0;
+  const int qt_start = down ? it.n_qt - 1 : it.qt_first;
+  const int64_t roff0 = (int64_t)(it.q_row_seg + qt_start * BM) * q_stride + (int64_t)(kvh * G) * D;
+  const int64_t rv0 = ((int64_t)(kvh * G) * p.total_q_tiles + it.q_tile0) * 64 + qt_start * BM;
   const char* d_q = reinterpret_cast<const char*>(p.q + roff0);
   const char* d_g = reinterpret_cast<const char*>(p.d_o + roff0);
   const char* d_r = reinterpret_cast<const char*>(((wave & 1) ? p.dsp : p.lse2p) + rv0);
-  const int64_t tile_bytes = (int64_t)BM * q_stride * 2;                 // to the next query tile of the same head
-  const int64_t head_bytes = (int64_t)D * 2 - (nqt - 1) * tile_bytes;    // to the first tile of the next head
-  const int64_t head_rows_bytes = (p.total_q_tiles * 64 - (int64_t)(nqt - 1) * BM) * 4;
-  int d_left = nqt, d_heads = G;
+  const int64_t head_bytes = (int64_t)D * 2;                             // to the next head of the group, same tile
+  const int64_t head_rows_bytes = p.total_q_tiles * 64 * 4;
+  const int64_t tile_bytes = (down ? -1 : 1) * (int64_t)BM * q_stride * 2 - (G - 1) * head_bytes;   // from the last head to the first, next tile
+  const int64_t tile_rows_bytes = (down ? -1 : 1) * (int64_t)BM * 4 - (G - 1) * head_rows_bytes;
+  int d_heads = G, d_tiles = nqt;
+  const int d_ragged = down ? nqt : 1;  // d_tiles while the segment's last query tile is the one to copy
   unsigned d_slot = 0;  // element offset of the ring slot inside the Q / dO rings (slot index x QT)
   const unsigned lane4 = (unsigned)lane * 4u;
   lds_f32* const rows_dst = (wave & 1) ? dsum_s : lse_s;
   auto dma_rows = [&]() __attribute__((always_inline)) { dma4(d_r + lane4, rows_dst + d_slot / (QT / RV)); };
   auto dma_piece = [&](int i) __attribute__((always_inline)) {
     const bool of_q = role == 0 ? i == 0 : i < PER_B / 2;
-    const unsigned voff = d_left == 1 ? v_last[i] : v_full[i];  // the segment's last query tile
+    const unsigned voff = d_tiles == d_ragged ? v_last[i] : v_full[i];  // the segment's last query tile
     const char* base = of_q ? d_q : d_g;
     lds_bf16* dst = L + (of_q ? Q_OFF : G_OFF) + piece_in_tile(i) * 512 + d_slot;
     dma16(base + voff, dst);
   };
   auto dma_advance = [&]() __attribute__((always_inline)) {
-    if (__builtin_expect(d_left > 1, 1)) {
-      --d_left;
-      d_q += tile_bytes; d_g += tile_bytes; d_r += BM * 4;
-    } else {  // on to the next head of the group; after the last stage, stay on it
-      const bool more = d_heads > 1;
-      d_heads -= more ? 1 : 0;
-      d_left = more ? nqt : 1;
-      const int64_t hb = more ? head_bytes : 0, hr = more ? head_rows_bytes : 0;
-      d_q += hb; d_g += hb; d_r += hr;
+    if (d_heads > 1) {
+      --d_heads;
+      d_q += head_bytes; d_g += head_bytes; d_r += head_rows_bytes;
+    } else {  // on to the next query tile; after the last stage, stay on it
+      const bool more = d_tiles > 1;
+      d_tiles -= more ? 1 : 0;
+      d_heads = more ? G : 1;
+      const int64_t tb = more ? tile_bytes : 0, tr = more ? tile_rows_bytes : 0;
+      d_q += tb; d_g += tb; d_r += tr;
     }
     d_slot = d_slot == (unsigned)((NS - 1) * QT) ? 0u : d_slot + (unsigned)QT;
   };
@@ -890,7 +899,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
     // pipeline state
     int sA = ROLE ? NS - 2 : 0;  // slot of stage g - 2 ROLE (rows operand); one before: row values and the next step's
                                  // transposed operand; two before: this step's transposed operand
-    int s_qt = it.qt_first;      // role A: query tile of stage g (whose S is computed in step g)
+    int s_qt = qt_start;         // role A: query tile of stage g (whose S is computed in step g)
+    int s_heads = G;             //         and the heads of that tile still to come, counting stage g's
     // Role A masks through the accumulator: the first MFMA of S starts from a tile that holds -inf where the query
     // does not see the key (and everywhere for a stage past the end of the walk) and 0 elsewhere.  The tile is
     // rebuilt only for the stages that need it.
@@ -1088,7 +1098,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
         if constexpr (m == 14) {  // bookkeeping for the next step (the copies of this step have been issued)
           dma_advance();
           sA = sA == NS - 1 ? 0 : sA + 1;
-          if (ROLE == 0 && ++s_qt == it.n_qt) s_qt = it.qt_first;
+          if (ROLE == 0 && --s_heads == 0) {
+            s_heads = G;
+            s_qt += down ? -1 : 1;
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       });
@@ -1667,7 +1680,10 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
       P.fplan = plan_fused(d, dkv_keys(d->head_dim), kNumXcd, fused_num_bufs(d, dkv_keys(d->head_dim)));
     } else {
       P.dq_items = plan_dq(d, dq_rows);
-      P.dkv_items = plan_dkv(d, dkv_keys(d->head_dim));
+      // head_dim 128: the pipelined kernel walks either way; the key blocks of one key/value head that run at the same time
+      // are the workgroups of the launch (one per CU) over the number of key/value heads
+      const int side_by_side = d->head_dim == 128 ? std::max(1, persistent_grid(0x7fffffff) / d->num_kv_heads) : 0;
+      P.dkv_items = plan_dkv(d, dkv_keys(d->head_dim), side_by_side);
     }
     P.qjobs = tile_jobs(d, false, 64, nullptr);
     P.kjobs = tile_jobs(d, true, 32, nullptr);

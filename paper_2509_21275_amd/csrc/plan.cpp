@@ -123,7 +123,41 @@ std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows) {
   return items;
 }
 
-std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys) {
+// Order and walk directions of one sequence's key blocks, given in key order (= longest walk first), when `width` of
+// them run side by side and read the same stream of query rows through one L2.  Blocks that start together stay
+// together only if they start at the same row; blocks of unequal length end at different times.  So:
+//   * blocks that every query sees come first, walking upwards: equal walks, started together at the first row;
+//   * of the others (walks that begin at the block's diagonal and all end at the last row) the longest `width` walk
+//     DOWN from the last row, started together; as each ends, at its diagonal, its workgroup takes the partner that
+//     makes the pair's length the same for all -- the shortest remaining walks, longest of them first, walking UP:
+//     a block that ends its descent at row r after time T - r is followed by one that starts its ascent near the row
+//     where the others are by then; all of them arrive at the last row together, and the next `width` longest descend;
+//   * the shortest quarter is kept for the end, longest first, walking upwards: small items for the workgroups to
+//     even out what their unequal speeds have left.
+// The result holds indices into the input order; reverse[i] is the direction of input block i.
+void side_by_side_order(const std::vector<DkvItem>& blocks, int width, std::vector<int>& order, std::vector<char>& reverse) {
+  const int n = (int)blocks.size();
+  order.clear();
+  reverse.assign(n, 0);
+  int lo = 0;
+  while (lo < n && blocks[lo].qt_first == 0 && blocks[lo].j0 + blocks[lo].kv_rows <= blocks[lo].ctx) order.push_back(lo++);
+  int hi = n - (n - lo) / 4;
+  const int tail = hi;
+  while (lo < hi) {
+    const int m = hi - lo;
+    const int down = m >= 2 * width ? width : (m + 1) / 2, up = std::min(down, m - down);
+    for (int i = 0; i < down; ++i) {
+      order.push_back(lo + i);
+      reverse[lo + i] = 1;
+    }
+    for (int i = 0; i < up; ++i) order.push_back(hi - up + i);
+    lo += down;
+    hi -= up;
+  }
+  for (int i = tail; i < n; ++i) order.push_back(i);
+}
+
+std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys, int side_by_side) {
   std::vector<DkvItem> items;
   int32_t q_tile0 = 0;
   for (int t = 0; t < d->num_segments; ++t) {
@@ -148,7 +182,24 @@ std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys) {
   // sequence by sequence, longest first; the key blocks of a sequence in key order, which is longest walk first (see
   // by_sequence_then_walk)
   std::stable_sort(items.begin(), items.end(), [](const DkvItem& a, const DkvItem& b) { return a.n_qt > b.n_qt; });
-  return items;
+  if (side_by_side <= 0) return items;
+  std::vector<DkvItem> out;
+  out.reserve(items.size());
+  std::vector<DkvItem> seq;
+  std::vector<int> order;
+  std::vector<char> reverse;
+  for (size_t i = 0; i < items.size();) {
+    size_t e = i;
+    while (e < items.size() && items[e].q_row_seg == items[i].q_row_seg && items[e].kv_row0 - items[e].j0 == items[i].kv_row0 - items[i].j0) ++e;
+    seq.assign(items.begin() + i, items.begin() + e);
+    side_by_side_order(seq, side_by_side, order, reverse);
+    for (int k : order) {
+      out.push_back(seq[k]);
+      out.back().reverse = reverse[k];
+    }
+    i = e;
+  }
+  return out;
 }
 
 int fused_num_bufs(const chunk_attn_desc* d, int keys) {

@@ -53,7 +53,8 @@ struct DkvItem {
   int32_t qt_first;   // first 32-row query tile (inside the segment) that sees a key of this tile
   int32_t n_qt;       // number of 32-row query tiles of the segment
   int32_t q_tile0;    // index of the segment's first 64-row tile in the padded per-row arrays (LSE, D)
-  int32_t pad0, pad1, pad2;
+  int32_t reverse;    // 1: the kernel walks the query tiles from the segment's last one down to qt_first (plan_dkv)
+  int32_t pad0, pad1;
 };
 
 // Work item of the one-pass backward kernel (head_dim 128): a DkvItem plus what the kernel needs to add its share of dQ
@@ -95,7 +96,10 @@ int64_t pair_count(const chunk_attn_desc* d);
 // Tiles of `tile_rows` query rows per segment, most work first.
 std::vector<FwdItem> plan_fwd(const chunk_attn_desc* d, int tile_rows);
 std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows);
-std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys);  // `keys` consecutive key rows per item
+// `keys` consecutive key rows per item.  `side_by_side` = 0: every item walks its query tiles upwards.  > 0: the number
+// of items of one key/value head that run at the same time; the items of a sequence are then ordered, and given a walk
+// direction each, so that those items read the same query rows at about the same time (see plan.cpp).
+std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys, int side_by_side = 0);
 // `width`-row tiles of every segment's key range (kv = true) or query range (kv = false), in segment order;
 // seg_tile0[t] receives the image index of segment t's first tile.
 std::vector<TileJob> tile_jobs(const chunk_attn_desc* d, bool kv, int width, std::vector<int32_t>* seg_tile0);

@@ -62,9 +62,16 @@ static int check_plan_cover(unsigned seed) {
     for (const auto& it : chunk_attn::plan_dq(&d, tile_rows)) REQUIRE(cover_rows(got, it.q_row0, it.q_rows, it.kv_row0, it.n0, 32));
     REQUIRE(got == want);
   }
-  for (int keys : {32, 128}) {
+  // (the order and the walk directions chosen for key blocks that run side by side change neither the cover nor the
+  // number of items; without them every block walks upwards)
+  for (int variant = 0; variant < 5; ++variant) {
+    const int keys = variant == 0 ? 32 : 128;
+    const int side_by_side = variant < 2 ? 0 : variant == 2 ? 1 : variant == 3 ? 3 : 32;
     std::vector<uint8_t> got((size_t)tq * tkv, 0);
-    for (const auto& it : chunk_attn::plan_dkv(&d, keys)) {
+    const auto dkv_items = chunk_attn::plan_dkv(&d, keys, side_by_side);
+    REQUIRE(dkv_items.size() == chunk_attn::plan_dkv(&d, keys).size());
+    for (const auto& it : dkv_items) {
+      REQUIRE(it.reverse == 0 || (it.reverse == 1 && side_by_side > 0));
       REQUIRE(it.kv_rows >= 1 && it.kv_rows <= keys && it.qt_first >= 0 && it.qt_first < it.n_qt);
       REQUIRE(it.n_qt == (it.q_len + 31) / 32);
       for (int qt = it.qt_first; qt < it.n_qt; ++qt) {  // the 32-row query tiles the kernel walks

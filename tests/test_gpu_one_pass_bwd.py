@@ -1,15 +1,23 @@
 """The one-pass backward for head_dim 128 (mode 2 of chunk_attn_test_set_bwd_mode): dK, dV and dQ from one walk over
 the keys, dQ added into float32 tiles in a fixed order along chains of key blocks (paper section 2.1: the gradient of a
 query sums over all keys it sees, that of a key over all queries that see it).  Against the oracle on the edge cases and
-on the scaled replicas of the workloads (one, two and four sub-chains per chain), bit-equality of dK / dV with the
-two-kernel backward (same arithmetic), bit-reproducibility, the accumulate and float32 variants, a clean status word,
-and sampled rows at full size."""
+on the scaled replicas of the workloads (one, two and four sub-chains per chain), dK / dV against the two-kernel
+backward (the same products, summed over the query tiles in another order: the two-kernel backward walks some key
+blocks downwards), bit-reproducibility, the accumulate and float32 variants, a clean status word, and sampled rows at
+full size."""
 import numpy as np
 import pytest
 import torch
 
 import synth
 import paper_2509_21275_amd as ca
+
+# dK / dV of the two backwards: float32 sums of the same terms in two orders, then one rounding to bf16 (2^-8 relative)
+TOL_ORDER = 1e-2
+
+
+def same_up_to_order(a, b):
+    return rel_err(a, b.double().cpu().numpy()) <= TOL_ORDER
 from gpu_util import TOL_GRAD, make_inputs, rel_err
 
 pytestmark = pytest.mark.gpu
@@ -63,7 +71,7 @@ def test_edge_cases_against_oracle_and_two_kernel_backward(oracle_mod, name, seg
     dq2, dk2, dv2, st = run_bwd(case, 2, q, k, v, do)
     dq1, dk1, dv1, _ = run_bwd(case, 1, q, k, v, do)
     assert st == 0
-    assert torch.equal(dk1, dk2) and torch.equal(dv1, dv2)      # the same arithmetic in the same order
+    assert same_up_to_order(dk1, dk2) and same_up_to_order(dv1, dv2)
     orc = oracle_mod.Oracle(case.segs, q.cpu(), k.cpu(), v.cpu(), do.cpu(), case.scale)
     dQ, dK, dV = orc.backward()
     errs = (rel_err(dq2, dQ), rel_err(dk2, dK), rel_err(dv2, dV))
@@ -92,18 +100,18 @@ def test_accumulate_and_float32_buffers():
     for f32 in (False, True):
         a = run_bwd(case, 2, q, k, v, do, accumulate=True, init=init, f32kv=f32)
         b = run_bwd(case, 1, q, k, v, do, accumulate=True, init=init, f32kv=f32)
-        assert a[3] == 0 and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+        assert a[3] == 0 and same_up_to_order(a[1], b[1]) and same_up_to_order(a[2], b[2])
         assert rel_err(a[0], b[0].double().cpu().numpy()) <= 2e-2   # dQ: two float32 summation orders, rounded to bf16
 
 
 def test_full_size_split_slice_sampled(oracle_mod):
     """The 32K split chunk at full size: 256 key blocks per chain (four sub-chains of 64), dQ on sampled rows against the
-    oracle, dK / dV bit-equal to the two-kernel backward, twice the same bits."""
+    oracle, dK / dV equal to the two-kernel backward's up to the order of the sums, twice the same bits."""
     case = synth.case_by_index(2)
     q, k, v, do = make_inputs(case)
     dq2, dk2, dv2, st = run_bwd(case, 2, q, k, v, do)
     dq1, dk1, dv1, _ = run_bwd(case, 1, q, k, v, do)
-    assert st == 0 and torch.equal(dk1, dk2) and torch.equal(dv1, dv2)
+    assert st == 0 and same_up_to_order(dk1, dk2) and same_up_to_order(dv1, dv2)
     rng = np.random.default_rng(case.seed + 3)
     rows = np.array(sorted({0, 1, 31, 32, 33, 127, 128, 4095, 4096, case.total_q - 1} | {int(x) for x in rng.integers(0, case.total_q, 20)}),
                     dtype=np.int32)
