@@ -75,6 +75,10 @@ def main():
                 row(base, f"{base.name}, one-pass backward")
             finally:
                 ca.chunk_attn_test_set_bwd_mode(0)
+    # what this machine sustains on matrix instructions alone (boxes differ by several per cent): the yardstick for the rows above
+    rate = ca.chunk_attn_measure_mfma_rate(500)
+    lines += ["", f"MFMA-only rate of the box these rows were measured on (chunk_attn_measure_mfma_rate, right after them): {rate:.0f} TFLOP/s."]
+    print(lines[-1], flush=True)
     text = "\n".join(lines) + "\n"
     if args.markdown:
         with open(args.markdown, "w") as fh:
