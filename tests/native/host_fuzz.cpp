@@ -139,7 +139,31 @@ static int check_plan_cover(unsigned seed) {
   return 0;
 }
 
+// The order and walk directions of key blocks that run side by side, worked out by hand for one slice of a split
+// sequence: 1024 context tokens and 16384 own tokens, 128 keys per block, 32 blocks at a time.  Blocks 0 .. 7 lie in
+// the context (every query sees them): first, upwards.  Of the 128 others the shortest quarter, 104 .. 135, is kept
+// for the end.  Of 8 .. 103 the 32 longest (8 .. 39) walk down, then their partners from the short end (72 .. 103, the
+// longest of them first) walk up; the 32 left over split in two: 40 .. 55 down, 56 .. 71 up.
+static int check_side_by_side_example() {
+  const unsigned seed = 0;  // (not a seeded case; REQUIRE prints it)
+  chunk_attn_seg s{0, 16384, 0, 16384 + 1024};
+  chunk_attn_desc d{64, 8, 128, 16384, 16384 + 1024, 1, &s, 0.1f};
+  const auto items = chunk_attn::plan_dkv(&d, 128, 32);
+  REQUIRE(items.size() == 136);
+  std::vector<int> want_block, want_rev;
+  auto put = [&](int lo, int hi, int rev) { for (int b = lo; b <= hi; ++b) { want_block.push_back(b); want_rev.push_back(rev); } };
+  put(0, 7, 0); put(8, 39, 1); put(72, 103, 0); put(40, 55, 1); put(56, 71, 0); put(104, 135, 0);
+  for (size_t i = 0; i < items.size(); ++i) {
+    REQUIRE(items[i].j0 == 128 * want_block[i] && items[i].reverse == want_rev[i]);
+    // The shortest of the descending walks ends first and its workgroup takes the first (longest) ascending one, the
+    // longest takes the last: every such pair covers the same number of query tiles (block b walks 512 - 4 (b - 8)).
+    if (i >= 8 && i < 40) REQUIRE((items[i].n_qt - items[i].qt_first) + (items[79 - i].n_qt - items[79 - i].qt_first) == 644);
+  }
+  return 0;
+}
+
 int main(int argc, char** argv) {
+  if (check_side_by_side_example()) return 1;
   const unsigned n_cases = argc > 1 ? (unsigned)std::atoi(argv[1]) : 200;
   int n_infeasible = 0, n_ckpt = 0;
   for (unsigned seed = 1; seed <= n_cases; ++seed) {
