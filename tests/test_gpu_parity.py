@@ -53,6 +53,10 @@ EDGE = [
     ("d128_tiny_walks", [(0, 32, 0, 32), (32, 33, 32, 33), (65, 64, 65, 64), (129, 1, 129, 129), (130, 95, 258, 95)], 2, 2, 128),
     # several segments with a context each, key ranges of 127 / 128 / 129 rows around a workgroup's 128 keys
     ("d128_many_contexts", [(0, 40, 0, 127), (40, 40, 127, 128), (80, 40, 255, 129), (120, 200, 384, 513)], 8, 2, 128),
+    # 64 key/value heads: four key blocks of a head run side by side, so the 12 + 2 key blocks of the long sequence go
+    # through every branch of the host's ordering (context blocks upwards, groups walking down with partners walking up,
+    # the leftover split in two, the shortest quarter last), next to a sequence with a single block
+    ("d128_two_way_walks", [(0, 1500, 0, 1500 + 200), (1500, 90, 1700, 90)], 64, 64, 128),
     # head_dim 256 (a variant of the path: other head dimensions)
     ("d256_one_token", [(0, 1, 0, 1)], 2, 2, 256),
     ("d256_ragged_tail_slice", [(0, 130, 0, 1000)], 8, 2, 256),
