@@ -58,6 +58,15 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
   r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
   return r;
 }
+// x * s element by element, rounded to bf16 (nearest even).  The head_dim 128 kernels fold the softmax scale (times
+// log2 e) into Q this way, in every place that forms Q K^T -- forward, its second pass, dQ kernel, and the copy of Q
+// the backward's pre-pass writes for the dK/dV kernels -- so that all of them see bit-identical scores.
+__device__ __forceinline__ bf16x8 scaled_bf16(bf16x8 x, float s) {
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (__bf16)((float)x[i] * s);
+  return r;
+}
 __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) {
   bf16x4 r;
   r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
