@@ -27,12 +27,6 @@
  *   lse           : [num_q_heads][total_q] float32, natural-log sum of exp of the scaled scores
  * Query head h uses key/value head h / (num_q_heads / num_kv_heads).
  *
- * Arithmetic: bf16 operands into the matrix units, fp32 accumulation, softmax in fp32, P and dS rounded to bf16 for the
- * second contraction of each pair.  For head_dim 64 and 256 the scale multiplies the fp32 scores.  For head_dim 128 (and
- * 96, which runs as 128) forward and backward multiply Q by scale * log2(e) and round to bf16 BEFORE the product -- the
- * same rounding in every kernel, so that forward and backward see the same scores -- which perturbs each score, and LSE
- * with it, by a relative 2^-8 at most (about 2e-3 nats on unit-variance inputs).
- *
  * All calls are asynchronous: they enqueue work on `stream` (a hipStream_t passed as
  * void*; NULL is the default stream) and return.  The segment table is a HOST pointer and
  * is only read during the call.  The library allocates no device memory: scratch space is
@@ -91,9 +85,8 @@ typedef struct {
 /*
  * Scratch sizes (bytes) for a descriptor: *fwd_bytes for chunk_attn_fwd, *bwd_bytes for
  * chunk_attn_bwd (the tile schedules, the row sums D_i = <dO_i, O_i>, and transposed
- * tile images of the operands; for head_dim 128 the backward's copy of Q with the scale folded
- * in, as large as Q; for head_dim 96 also zero-padded copies of the tensors, 128 wide).  Either
- * output pointer may be NULL.  Validates the descriptor.
+ * tile images of the operands; for head_dim 96 also zero-padded copies of the tensors, 128
+ * wide).  Either output pointer may be NULL.  Validates the descriptor.
  */
 int chunk_attn_workspace_bytes(const chunk_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
 

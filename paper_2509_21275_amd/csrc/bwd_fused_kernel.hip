@@ -499,7 +499,7 @@ __global__ __launch_bounds__(256, 1) void bwd_fused_pipe_kernel(FusedParams p) {
             asm volatile("" : "+v"(wu));
             pw[(j - 1) >> 3][(j - 1) & 7] = wu;
           }
-          e_hold[q] = __builtin_amdgcn_exp2f(cur[kb][i] * c + r4[i >> 2][i & 3]);  // r4 = -LSE log2 e
+          e_hold[q] = __builtin_amdgcn_exp2f(cur[kb][i] * c - r4[i >> 2][i & 3]);
           asm volatile("" : "+v"(e_hold[q]));
         } else {
           const float e = (float)ph[kb][i >> 3][i & 7] * (cur[kb][i] + r4[i >> 2][i & 3]);  // r4 = -D
@@ -779,7 +779,7 @@ __global__ __launch_bounds__(256) void zero_words_kernel(unsigned* __restrict__ 
 
 }  // namespace
 
-hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& P, const float* lse2p, const float* dsp, const __bf16* q_scaled,
+hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& P, const float* lse2p, const float* dsp,
                             hipStream_t stream) {
   constexpr int D = 128;
   char* ws = a.workspace;
@@ -791,9 +791,7 @@ hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const Bw
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   FusedParams p;
-  // Q with the softmax scale (times log2 e) folded in, as every head_dim 128 kernel sees it: S = Q' K^T is in log2 units,
-  // dK = dS^T Q' ln 2
-  p.q = q_scaled; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.lse2p = lse2p; p.dsp = dsp;
+  p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.lse2p = lse2p; p.dsp = dsp;
   p.dk = a.dk; p.dv = a.dv;
   p.items = reinterpret_cast<const FusedItem*>(ws + P.fitems_off);
   p.order = reinterpret_cast<const int32_t*>(ws + P.forder_off);
@@ -805,7 +803,7 @@ hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const Bw
   p.total_qt32 = P.qt32_tiles;
   p.buf_bytes = (int64_t)d->num_q_heads * P.qt32_tiles * 16384;
   p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = d->num_q_heads / d->num_kv_heads;
-  p.scale = 0.6931471805599453f; p.scale_log2 = 1.0f;
+  p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * 1.4426950408889634f;
   p.accumulate = a.accumulate ? 1 : 0;
   p.out_f32 = a.dkv_f32 ? 1 : 0;
   p.spin_limit = 1 << 20;

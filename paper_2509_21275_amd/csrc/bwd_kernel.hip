@@ -39,15 +39,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 // bwd_pre: one workgroup per (64-row query tile, head); D / 8 threads per row, one 16-byte chunk of O and of dO each, so
 // that a wave reads whole rows (the kernel is bound by memory: it reads O and dO once).
 // ------------------------------------------------------------------------------------------------
-// It also writes -LSE log2 e per row (-inf for the rows that pad a tile: their P is 0) and, when `qs` is given, the copy
-// of Q that carries the softmax scale: qs = bf16(q * q_scale), same layout as q (scaled_bf16: the very rounding the
-// forward and the dQ kernel apply to their Q fragments, so that every kernel forms the same scores).
 template <int D>
 __global__ __launch_bounds__(256) void bwd_pre_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o,
                                                       const float* __restrict__ lse, const TileJob* __restrict__ jobs,
                                                       int64_t total_q_tiles, int total_q, int num_q_heads,
-                                                      float* __restrict__ lse2p, float* __restrict__ dsp,
-                                                      const __bf16* __restrict__ q, __bf16* __restrict__ qs, float q_scale) {
+                                                      float* __restrict__ lse2p, float* __restrict__ dsp) {
   constexpr int TPR = D / 8;         // threads per row
   constexpr int RPP = 256 / TPR;     // rows per pass
   const int head = blockIdx.x % num_q_heads;
@@ -64,14 +60,13 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(const __bf16* __restrict__
       const bf16x8 b = *reinterpret_cast<const bf16x8*>(d_o + base);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
-      if (qs != nullptr) *reinterpret_cast<bf16x8*>(qs + base) = scaled_bf16(*reinterpret_cast<const bf16x8*>(q + base), q_scale);
     }
 #pragma unroll
     for (int w = 1; w < TPR; w *= 2) acc += __shfl_xor(acc, w);
     if (part == 0) {
       const int64_t slot = ((int64_t)head * total_q_tiles + job.image) * 64 + r;
       dsp[slot] = valid ? -acc : 0.f;  // stored negated: the kernels add it (or start an accumulation from it)
-      lse2p[slot] = valid ? -lse[(int64_t)head * total_q + job.src_row0 + r] * kLog2e : -INFINITY;
+      lse2p[slot] = valid ? lse[(int64_t)head * total_q + job.src_row0 + r] * kLog2e : INFINITY;
     }
   }
 }
@@ -255,7 +250,7 @@ __global__ __launch_bounds__(WAVES * 64, D > 128 ? 1 : 8 / WAVES) void bwd_dq_ke
       // ---- P = exp2(S c - LSE), dS = P (dP - D); masked keys give P = 0 ----
       float pe[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) pe[i] = __builtin_amdgcn_exp2f(s[i] * c + lse2);  // lse2 = -LSE log2 e
+      for (int i = 0; i < 16; ++i) pe[i] = __builtin_amdgcn_exp2f(s[i] * c - lse2);
       if (BN * t + BN > it.n0 + wave_row0) {
         const int lim = it.n0 + wave_row0 + l32 - BN * t;  // visible iff local key index < lim
 #pragma unroll
@@ -333,6 +328,8 @@ struct DkvParams {
   int32_t accumulate;
   int32_t out_f32;      // dk / dv point to fp32 arrays of the same shape
   int32_t* taken;       // 8 block-queue counters of the pipelined kernel (zero before the launch)
+  int32_t* ended;       // per queue, the blocks that have ended (zero before the launch)
+  int32_t side_by_side; // blocks of a queue that run at the same time (DkvItem::in_step)
   unsigned long long* clock_log;  // null, or where the pipelined kernel's workgroups log their clocks
 };
 
@@ -540,7 +537,7 @@ __global__ __launch_bounds__(KB * 128, D > 128 ? 1 : 4 / KB) void bwd_dkv_kernel
         // P = exp2(S c - LSE); entries a query does not see give P = 0
         float w[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) w[i] = __builtin_amdgcn_exp2f(s[i] * c + r4[i >> 2][i & 3]);  // r4 = -LSE log2 e
+        for (int i = 0; i < 16; ++i) w[i] = __builtin_amdgcn_exp2f(s[i] * c - r4[i >> 2][i & 3]);
         if (i0 < jrel_lo + 31) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
@@ -752,7 +749,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   const int xcd = xcd_of_this_wave();
   clock_log_stamp(p.clock_log, 0);
   int blk = 0;
-  if (wave == 0) blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
+  // blocks that walk the same rows as the others of their group wait for the groups before them (DkvItem::in_step)
+  auto start_in_step = [&](int b) __attribute__((always_inline)) {
+    if (b >= 0 && p.items[b / p.num_kv_heads].in_step) wait_for_earlier_groups(p.ended, b, p.side_by_side);
+  };
+  if (wave == 0) {
+    blk = block_claim_finish(p.taken, num_blocks, xcd, block_claim_issue(p.taken, xcd));
+    start_in_step(blk);
+  }
   blk = broadcast_from_wave0(&next_block, blk);
   while (blk >= 0) {
   int pending_claim = 0;
@@ -760,6 +764,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   const DkvItem it = p.items[blk / p.num_kv_heads];
   const int G = p.group;
   const int64_t q_stride = (int64_t)p.num_q_heads * D, kv_stride = (int64_t)p.num_kv_heads * D;
+  const float c = p.scale_log2;
 
   // zero everything but the ring slots the prologue fills
   {
@@ -972,20 +977,19 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
             mask_c[1][i] = 8 * (i >> 2) + (i & 3) < lim1 ? -INFINITY : 0.f;
           }
           mask_set = true;
-        } else {
+        } else if (__builtin_expect(mask_set, 0)) {
+          mask_c[0] = zero16;
+          mask_c[1] = zero16;
           mask_set = false;
         }
       }
       // hand-over and row values are issued between the MFMAs of the first mini-steps, so that the matrix pipe restarts
       // right after the barrier; the vector work starts at mini-step 4
       bf16x8 ph[2][2];
-      // -LSE log2 e of stage g (role A: where the accumulation of S(g) starts, see below) or -D of stage g - 3 (role B),
-      // of rows 8 g4 + 4 hh + 0..3
-      f32x4 r4[4];
+      f32x4 r4[4];  // LSE (role A) or -D (role B) of rows 8 g4 + 4 hh + 0..3
       const unsigned pa = pex0 + (ROLE == 0 ? (g & 1) : ((g & 1) ^ 1)) * (PS * 2);
-      const unsigned ra = rv0 + (ROLE == 0 ? sA : sR) * (RV * 4);
+      const unsigned ra = rv0 + sR * (RV * 4);
       unsigned pw[2][8];
-      f32x16 lse_tile;
       float e_hold[2];  // role A: exponentials of the previous pair (converted one mini-step later: a transcendental
                         // result cannot be consumed by the very next instruction)
       // vector work of score 2 dw + q of block kb (pair j = 8 kb + dw), pinned to where it is written (the compiler
@@ -1001,7 +1005,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
             asm volatile("" : "+v"(wu));
             pw[(j - 1) >> 3][(j - 1) & 7] = wu;
           }
-          e_hold[q] = __builtin_amdgcn_exp2f(cur[kb][i]);  // S c - LSE already: Q carries c, the accumulation began at -LSE
+          e_hold[q] = __builtin_amdgcn_exp2f(cur[kb][i] * c - r4[i >> 2][i & 3]);
           asm volatile("" : "+v"(e_hold[q]));
         } else {
           const float e = (float)ph[kb][i >> 3][i & 7] * (cur[kb][i] + r4[i >> 2][i & 3]);  // r4 = -D
@@ -1045,15 +1049,6 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
           else fr[mm & 7] = load_t(n_lo, n_hi, std::integral_constant<int, mm - NF>{});
         }
         const bf16x8 fa = fr[m & 7];
-        if constexpr (ROLE == 0 && m == 5) {  // the row values have arrived (mini-step 4 waited for them)
-          lse_tile = __builtin_shufflevector(__builtin_shufflevector(r4[0], r4[1], 0, 1, 2, 3, 4, 5, 6, 7),
-                                             __builtin_shufflevector(r4[2], r4[3], 0, 1, 2, 3, 4, 5, 6, 7),
-                                             0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-          if (__builtin_expect(mask_set, 0)) {
-            mask_c[0] += lse_tile;
-            mask_c[1] += lse_tile;
-          }
-        }
         // S / dP live in vector registers (the vector work reads them directly) and K / V fragments in accumulation
         // registers; written as opaque instructions since the compiler keeps every MFMA result of a kernel with more
         // than 256 registers in accumulation registers.  Their results are first read one step later.
@@ -1064,14 +1059,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
             acc[kb][db] = mfma32(fa, f_old[kb][ks], acc[kb][db]);
           } else {
             constexpr int ks = m - 2 * DB;
-            if (ks == 0 && ROLE == 0) {
-              // S(g) starts from -LSE of its query rows (the row values just read, the same tile for both key blocks);
-              // on the few stages that need the mask, from -LSE + mask
-              if (__builtin_expect(mask_set, 0))
-                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]), "v"(mask_c[kb]));
-              else
-                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]), "v"(lse_tile));
-            } else if (ks == 0)
+            if (ks == 0 && ROLE == 0)
+              asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]), "v"(mask_c[kb]));
+            else if (ks == 0)
               asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]));
             else
               asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(nxt[kb]) : "v"(fa), "a"(bfrag[kb][ks]));
@@ -1175,7 +1165,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_pipe_kernel(DkvParams p, int n
   else body(std::integral_constant<int, 1>{});
   // on to the next block; the stores of the epilogue are not waited for here
   int nb = 0;
-  if (wave == 0) nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
+  if (wave == 0) {
+    if (lane == 0) __hip_atomic_fetch_add(p.ended + (blk & 7), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    nb = block_claim_finish(p.taken, num_blocks, xcd, pending_claim);
+    start_in_step(nb);
+  }
   blk = broadcast_from_wave0(&next_block, nb);
   }
   clock_log_stamp(p.clock_log, 1);
@@ -1352,28 +1346,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
   }
   // -D of the unit's row in every element of a tile: the accumulation of dP^T starts from it, so that the vector work
   // gets dP - D straight from the matrix pipe (a column of dP^T belongs to one query row)
-  // and -LSE likewise for S^T: Q carries the softmax scale (times log2 e), so the scores come out of the matrix pipe
-  // as S^T c - LSE and the vector work on them is the exponential alone
-  f32x16 dneg[2], lneg[2];
+  f32x16 dneg[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      dneg[u][i] = dsum[u];
-      lneg[u][i] = lse2[u];  // (stored negated)
-    }
+    for (int i = 0; i < 16; ++i) dneg[u][i] = dsum[u];
   // One wait the compiler can see for everything issued so far (loads complete in order: the copies have landed when
   // the fragments have), so that it puts no full waits for outstanding loads into the loop
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-#pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      qf[u][ks] = scaled_bf16(qf[u][ks], p.scale_log2);
-      // in their accumulation registers here and now: the MFMAs that read them are opaque to the compiler, which would
-      // otherwise be free to finish this right in front of them, closer than the hardware allows
-      asm volatile("" : "+a"(qf[u][ks]));
-    }
   wg_barrier();
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -1393,6 +1373,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int i = 0; i < 8; ++i) f[b][u][ks][i] = (__bf16)0.0f;
+  const float c = p.scale_log2;
   bf16x8 fr[8];  // ring of operand fragments
 
   // S^T(0) = K(0) Q^T, then the first fragments of step 0 (V rows of stage 0)
@@ -1405,7 +1386,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
     for (int ks = 0; ks < DK; ++ks)
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(x[0][u]) : "v"(a[ks]), "a"(qf[u][ks]), "v"(lneg[u]));
+        if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(x[0][u]) : "v"(a[ks]), "a"(qf[u][ks]));
         else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(x[0][u]) : "v"(a[ks]), "a"(qf[u][ks]));
       }
     mfma_settle();
@@ -1437,7 +1418,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
     auto exp_half = [&](auto j_c, auto q_c) __attribute__((always_inline)) {  // P of element 2 dw + q of unit u (pair j = 8 u + dw)
       constexpr int j = decltype(j_c)::value, q = decltype(q_c)::value;
       constexpr int u = j >> 3, i = 2 * (j & 7) + q;
-      float tt = cur[u][i];  // S^T c - LSE already
+      float tt = cur[u][i] * c - lse2[u];
       if (MASKED) {
         if (8 * (i >> 2) + (i & 3) >= lim[u]) tt = -INFINITY;
       }
@@ -1482,8 +1463,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_pipe_kernel(DqParams p, int num
           constexpr int ks = m - DK;
           f32x16& d_ = nxt[u];
           const bf16x8& b_ = qf[u][ks];
-          const f32x16& n_ = lneg[u];
-          if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d_) : "v"(a_), "a"(b_), "v"(n_));
+          if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d_) : "v"(a_), "a"(b_));
           else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d_) : "v"(a_), "a"(b_));
         } else {
           constexpr int ks = (m - 2 * DK) / DB, db = (m - 2 * DK) % DB;
@@ -1601,8 +1581,6 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
   float* lse2p = reinterpret_cast<float*>(ws + P.lse2p_off);
   float* dsp = reinterpret_cast<float*>(ws + P.dsp_off);
   __bf16* kt = reinterpret_cast<__bf16*>(ws + P.kt_off);
-  // head_dim 128: the copy of Q that carries the softmax scale, for the kernels that stream Q (written by the pre-pass)
-  __bf16* qs = D == 128 ? reinterpret_cast<__bf16*>(ws + P.qs_off) : nullptr;
   hipError_t e;
 
   // pre-pass: D, scaled LSE, transposed operand images
@@ -1610,7 +1588,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     const int64_t blocks = (int64_t)P.qjobs.size() * d->num_q_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL((bwd_pre_kernel<D>), dim3((unsigned)blocks), dim3(256), 0, stream, a.o, a.d_o, a.lse, qjobs,
-                       P.q_tiles, d->total_q, d->num_q_heads, lse2p, dsp, a.q, qs, d->softmax_scale * kLog2e);
+                       P.q_tiles, d->total_q, d->num_q_heads, lse2p, dsp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if constexpr (D != 128) {  // the head_dim 128 dQ kernel reads K^T from its K tiles
@@ -1631,7 +1609,7 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
 
   const int group = d->num_q_heads / d->num_kv_heads;
   if constexpr (D == 128) {
-    if (P.fused) return launch_bwd_fused(d, a, P, lse2p, dsp, qs, stream);
+    if (P.fused) return launch_bwd_fused(d, a, P, lse2p, dsp, stream);
   }
   {  // dQ
     DqParams p;
@@ -1664,15 +1642,15 @@ hipError_t launch_bwd_t(const chunk_attn_desc* d, const BwdArgs& a, const BwdPla
     DkvParams p;
     p.q = a.q; p.k = a.k; p.v = a.v; p.d_o = a.d_o; p.lse2p = lse2p; p.dsp = dsp;
     p.dk = a.dk; p.dv = a.dv;
-    if constexpr (D == 128) p.q = qs;  // S = Q' K^T comes out in log2 units; dK = dS^T Q' ln 2
     p.items = reinterpret_cast<const DkvItem*>(ws + P.dkv_items_off);
     p.total_q_tiles = P.q_tiles;
     p.num_q_heads = d->num_q_heads; p.num_kv_heads = d->num_kv_heads; p.group = group;
     p.scale = d->softmax_scale; p.scale_log2 = d->softmax_scale * kLog2e;
-    if constexpr (D == 128) p.scale = 0.6931471805599453f;
     p.accumulate = a.accumulate ? 1 : 0;
     p.out_f32 = a.dkv_f32 ? 1 : 0;
     p.taken = reinterpret_cast<int32_t*>(ws + P.queues_off) + kBlockQueues;
+    p.ended = p.taken + kBlockQueues;
+    p.side_by_side = std::max(1, persistent_grid(0x7fffffff) / kBlockQueues);
     p.clock_log = clock_log(2);
     static_assert(DKV_KEYS == 128, "the head_dim 64 and 128 kernels cover 128 keys per workgroup");
     const int64_t blocks = (int64_t)P.dkv_items.size() * d->num_kv_heads;
@@ -1742,7 +1720,7 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   P.q32jobs_off = P.forder_off + up256(n_fused * kNumXcd * sizeof(int32_t));
   // block-queue counters of the dQ and of the dK/dV kernel (zero in the blob)
   P.queues_off = P.q32jobs_off + (d->head_dim == 128 ? up256((size_t)P.qt32_tiles * sizeof(DqTileJob)) : 0);
-  P.blob_bytes = P.queues_off + up256(2 * kBlockQueues * sizeof(int32_t));
+  P.blob_bytes = P.queues_off + up256(3 * kBlockQueues * sizeof(int32_t));  // dQ queues, dK/dV queues, dK/dV blocks ended
   const size_t row_slots = (size_t)d->num_q_heads * P.q_tiles * 64;
   P.fprog_off = P.blob_bytes;
   // progress counters, then the status word (its own 256 bytes), then a scratch tile
@@ -1752,10 +1730,7 @@ void bwd_layout(const chunk_attn_desc* d, BwdPlan& P, bool with_plan) {
   P.kt_off = P.dsp_off + up256(row_slots * sizeof(float));
   // transposed K images only for head_dim 64 (the head_dim 128 dQ kernel reads K^T from its K tiles)
   // (256 bytes remain in any case: the dK/dV kernels copy the LSE / D rows 64 at a time, up to 32 past a segment's last)
-  // head_dim 128 instead: the copy of Q that carries the softmax scale
-  P.qs_off = P.kt_off + 256;
-  P.fdq_off = P.kt_off + (d->head_dim == 128 ? 256 + up256((size_t)d->total_q * d->num_q_heads * 128 * sizeof(__bf16))
-                                             : up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16)));
+  P.fdq_off = P.kt_off + (d->head_dim == 128 ? 256 : up256((size_t)d->num_kv_heads * P.kv32_tiles * 32 * d->head_dim * sizeof(__bf16)));
   P.total = P.fdq_off + (d->head_dim == 128 ? (size_t)fused_num_bufs(d, dkv_keys(128)) * d->num_q_heads * P.qt32_tiles * 4096 * sizeof(float) : 0);
 }
 

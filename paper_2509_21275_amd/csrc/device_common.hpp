@@ -58,15 +58,6 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
   r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
   return r;
 }
-// x * s element by element, rounded to bf16 (nearest even).  The head_dim 128 kernels fold the softmax scale (times
-// log2 e) into Q this way, in every place that forms Q K^T -- forward, its second pass, dQ kernel, and the copy of Q
-// the backward's pre-pass writes for the dK/dV kernels -- so that all of them see bit-identical scores.
-__device__ __forceinline__ bf16x8 scaled_bf16(bf16x8 x, float s) {
-  bf16x8 r;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) r[i] = (__bf16)((float)x[i] * s);
-  return r;
-}
 __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) {
   bf16x4 r;
   r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
@@ -139,6 +130,20 @@ __device__ __forceinline__ int block_claim_finish(int32_t* taken, int total, int
 }
 // Hands a wave-uniform value of wave 0 to the whole workgroup through `slot` (LDS).  Contains a workgroup barrier
 // without a memory fence: outstanding global stores are not waited for.
+// Blocks that read the same rows side by side (one queue = one key/value head's blocks, `width` of them at a time): a
+// block marked for it starts only when `ended[queue]`, the number of the queue's blocks that have ended, has reached the
+// first index of its group of `width`.  Called by one wave for block `blk` (>= 0); the wait is bounded (the blocks
+// waited for were claimed earlier and are running, so it ends by itself; the bound only keeps a surprise from turning
+// into a hang) and nothing but timing depends on it.
+__device__ __forceinline__ void wait_for_earlier_groups(const int32_t* ended, int blk, int width) {
+  const int need = (blk / 8) / width * width;
+  if (need == 0) return;
+  for (int spins = 0; spins < 256; ++spins) {
+    const int seen = __hip_atomic_load(ended + (blk & 7), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (__builtin_amdgcn_readfirstlane(seen) >= need) break;
+    __builtin_amdgcn_s_sleep(32);
+  }
+}
 __device__ __forceinline__ int broadcast_from_wave0(int* slot, int value) {
   if (threadIdx.x == 0) *(volatile int*)slot = value;
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)

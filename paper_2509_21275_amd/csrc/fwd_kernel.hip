@@ -111,10 +111,7 @@ __global__ __launch_bounds__(WAVES * 64, D > 128 ? 1 : 8 / WAVES) void fwd_kerne
     const int r = min(wave_row0 + 32 * qb + l32, it.q_rows - 1);  // rows past the tile repeat the last one (never stored)
     const __bf16* qp = p.q + (int64_t)(it.q_row0 + r) * q_stride + (int64_t)head * D + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-      if constexpr (D == 128) qf[qb][ks] = scaled_bf16(qf[qb][ks], p.scale_log2);  // as the pipelined forward does
-    }
+    for (int ks = 0; ks < DK; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
 
   f32x16 oacc[QB][DB];
@@ -127,7 +124,7 @@ __global__ __launch_bounds__(WAVES * 64, D > 128 ? 1 : 8 / WAVES) void fwd_kerne
   float m_run[QB], l_run[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
-  const float c = D == 128 ? 1.0f : p.scale_log2;
+  const float c = p.scale_log2;
 
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -440,12 +437,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      qf[u][ks] = scaled_bf16(lds_chunk<KC>(stage, 32 * u + l32, 2 * ks + hh), p.scale_log2);
-      // in their accumulation registers here and now: the MFMAs that read them are opaque to the compiler, which would
-      // otherwise be free to finish this right in front of them, closer than the hardware allows
-      asm volatile("" : "+a"(qf[u][ks]));
-    }
+    for (int ks = 0; ks < DK; ++ks) qf[u][ks] = lds_chunk<KC>(stage, 32 * u + l32, 2 * ks + hh);
   wg_barrier();
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -464,11 +456,11 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int i = 0; i < 8; ++i) f[b][u][ks][i] = (__bf16)0.0f;
+  const float c = p.scale_log2;
   bf16x8 fr[8];  // ring of operand fragments
 
   // S^T(0) = K(0) Q^T and the reference maximum of each row; then the first fragments of step 0 (zeros)
   float mc[2], l_run[2];
-  f32x16 minus_m[2];  // -m in every element: where the accumulation of S^T starts from the second stage on
   {
     bf16x8 a[DK];
     static_for<0, DK>([&](auto ks_c) __attribute__((always_inline)) { a[decltype(ks_c)::value] = load_rows(k_ev0, k_od0, ks_c); });
@@ -497,13 +489,8 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
         const int j = 8 * (i >> 2) + 4 * hh + (i & 3);
         if (j < lim) mx = fmaxf(mx, x[0][u][i]);
       }
-      mc[u] = max_halves(mx);
+      mc[u] = max_halves(mx) * c;
       l_run[u] = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        x[0][u][i] -= mc[u];
-        minus_m[u][i] = -mc[u];
-      }
     }
   }
   bool risk = false;
@@ -550,7 +537,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
       constexpr int j = decltype(j_c)::value, q = decltype(q_c)::value;
       constexpr int u = j >> 3, i = 2 * (j & 7) + q;
       if constexpr (j > 0 && q == 0) finish_pair(j - 1);
-      float tt = cur[u][i];  // S^T - m already: Q carries the scale, the accumulation started at -m
+      float tt = cur[u][i] * c - mc[u];
       if (MASKED) {
         if (8 * (i >> 2) + (i & 3) >= lim[u]) tt = -INFINITY;
       }
@@ -579,8 +566,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(FwdParams p, int num_b
           const bf16x8& a_ = fa;  // (named references: variables used only inside an asm statement are not captured)
           f32x16& d_ = nxt[u];
           const bf16x8& b_ = qf[u][ks];
-          const f32x16& c_ = minus_m[u];
-          if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d_) : "v"(a_), "a"(b_), "v"(c_));
+          if (ks == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d_) : "v"(a_), "a"(b_));
           else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d_) : "v"(a_), "a"(b_));
         }
       };

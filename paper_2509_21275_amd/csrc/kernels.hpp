@@ -87,7 +87,7 @@ struct BwdPlan {
   std::vector<TileJob> qjobs, kjobs;
   int64_t q_tiles = 0, kv32_tiles = 0;
   size_t dq_items_off = 0, dkv_items_off = 0, qjobs_off = 0, kjobs_off = 0, queues_off = 0, blob_bytes = 0;
-  size_t lse2p_off = 0, dsp_off = 0, kt_off = 0, qs_off = 0, total = 0;
+  size_t lse2p_off = 0, dsp_off = 0, kt_off = 0, total = 0;
   // one-pass backward (head_dim 128): its items and workgroup order travel at the end of the blob; then the per-wave
   // progress counters and the status word (cleared by a kernel on every call) and the float32 dQ tiles
   bool fused = false;
@@ -104,7 +104,7 @@ int bwd_mode();
 // of kernel `which` in it (0 forward, 1 dQ, 2 dK/dV), kClockLogEntries values of 8 bytes each.
 constexpr size_t kClockLogEntries = 4 * 1024;
 unsigned long long* clock_log(int which);
-hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& plan, const float* lse2p, const float* dsp, const __bf16* q_scaled,
+hipError_t launch_bwd_fused(const chunk_attn_desc* d, const BwdArgs& a, const BwdPlan& plan, const float* lse2p, const float* dsp,
                             hipStream_t stream);
 // Fills the offsets (and, if with_plan, the schedules) for a validated descriptor.
 void bwd_layout(const chunk_attn_desc* d, BwdPlan& plan, bool with_plan);

@@ -135,12 +135,20 @@ std::vector<DqItem> plan_dq(const chunk_attn_desc* d, int tile_rows) {
 //   * the shortest quarter is kept for the end, longest first, walking upwards: small items for the workgroups to
 //     even out what their unequal speeds have left.
 // The result holds indices into the input order; reverse[i] is the direction of input block i.
-void side_by_side_order(const std::vector<DkvItem>& blocks, int width, std::vector<int>& order, std::vector<char>& reverse) {
+// in_step[i]: block i is one of the equal walks at the front.  The workgroups that run them drift apart over many blocks
+// (left alone their speeds differ by up to 2 %), until they no longer find each other's rows in the L2; the kernel
+// therefore starts such a block only when the blocks of the groups of `width` before it have ended.
+void side_by_side_order(const std::vector<DkvItem>& blocks, int width, std::vector<int>& order, std::vector<char>& reverse,
+                        std::vector<char>& in_step) {
   const int n = (int)blocks.size();
   order.clear();
   reverse.assign(n, 0);
+  in_step.assign(n, 0);
   int lo = 0;
-  while (lo < n && blocks[lo].qt_first == 0 && blocks[lo].j0 + blocks[lo].kv_rows <= blocks[lo].ctx) order.push_back(lo++);
+  while (lo < n && blocks[lo].qt_first == 0 && blocks[lo].j0 + blocks[lo].kv_rows <= blocks[lo].ctx) {
+    in_step[lo] = 1;
+    order.push_back(lo++);
+  }
   int hi = n - (n - lo) / 4;
   const int tail = hi;
   while (lo < hi) {
@@ -187,15 +195,16 @@ std::vector<DkvItem> plan_dkv(const chunk_attn_desc* d, int keys, int side_by_si
   out.reserve(items.size());
   std::vector<DkvItem> seq;
   std::vector<int> order;
-  std::vector<char> reverse;
+  std::vector<char> reverse, in_step;
   for (size_t i = 0; i < items.size();) {
     size_t e = i;
     while (e < items.size() && items[e].q_row_seg == items[i].q_row_seg && items[e].kv_row0 - items[e].j0 == items[i].kv_row0 - items[i].j0) ++e;
     seq.assign(items.begin() + i, items.begin() + e);
-    side_by_side_order(seq, side_by_side, order, reverse);
+    side_by_side_order(seq, side_by_side, order, reverse, in_step);
     for (int k : order) {
       out.push_back(seq[k]);
       out.back().reverse = reverse[k];
+      out.back().in_step = in_step[k];
     }
     i = e;
   }

@@ -54,7 +54,8 @@ struct DkvItem {
   int32_t n_qt;       // number of 32-row query tiles of the segment
   int32_t q_tile0;    // index of the segment's first 64-row tile in the padded per-row arrays (LSE, D)
   int32_t reverse;    // 1: the kernel walks the query tiles from the segment's last one down to qt_first (plan_dkv)
-  int32_t pad0, pad1;
+  int32_t in_step;    // 1: started only when the blocks of the groups before it (of `side_by_side` blocks) have ended (plan_dkv)
+  int32_t pad1;
 };
 
 // Work item of the one-pass backward kernel (head_dim 128): a DkvItem plus what the kernel needs to add its share of dQ

@@ -72,6 +72,7 @@ static int check_plan_cover(unsigned seed) {
     REQUIRE(dkv_items.size() == chunk_attn::plan_dkv(&d, keys).size());
     for (const auto& it : dkv_items) {
       REQUIRE(it.reverse == 0 || (it.reverse == 1 && side_by_side > 0));
+      REQUIRE(it.in_step == 0 || (it.in_step == 1 && side_by_side > 0 && it.reverse == 0 && it.qt_first == 0));
       REQUIRE(it.kv_rows >= 1 && it.kv_rows <= keys && it.qt_first >= 0 && it.qt_first < it.n_qt);
       REQUIRE(it.n_qt == (it.q_len + 31) / 32);
       for (int qt = it.qt_first; qt < it.n_qt; ++qt) {  // the 32-row query tiles the kernel walks
@@ -155,6 +156,7 @@ static int check_side_by_side_example() {
   put(0, 7, 0); put(8, 39, 1); put(72, 103, 0); put(40, 55, 1); put(56, 71, 0); put(104, 135, 0);
   for (size_t i = 0; i < items.size(); ++i) {
     REQUIRE(items[i].j0 == 128 * want_block[i] && items[i].reverse == want_rev[i]);
+    REQUIRE(items[i].in_step == (want_block[i] < 8 ? 1 : 0));  // the equal walks of the context start group by group
     // The shortest of the descending walks ends first and its workgroup takes the first (longest) ascending one, the
     // longest takes the last: every such pair covers the same number of query tiles (block b walks 512 - 4 (b - 8)).
     if (i >= 8 && i < 40) REQUIRE((items[i].n_qt - items[i].qt_first) + (items[79 - i].n_qt - items[79 - i].qt_first) == 644);

@@ -127,7 +127,4 @@ def test_forward_scores_outgrow_first_tile(oracle_mod):
     k = (k.float() * 0.05 + ramp).to(torch.bfloat16)                        # up to ~136 nats at the last key
     eo, el = _forward_only(oracle_mod, case, q, k, v)
     print("growing scores", eo, el, flush=True)
-    # The head_dim 128 kernels fold the softmax scale into Q before the product, rounded to bf16: every score, and with it
-    # LSE, carries a relative error of up to 2^-8 on top of the absolute tolerance -- here, with all q equal, the same
-    # for every score (4 scale log2(e) = 0.51007 becomes 0.51172), which is the worst case.  LSE reaches 136 nats.
-    assert eo <= TOL_O and el <= 5e-2 + 2.0 ** -8 * 136.0
+    assert eo <= TOL_O and el <= 5e-2
