@@ -57,6 +57,8 @@ EDGE = [
     # through every branch of the host's ordering (context blocks upwards, groups walking down with partners walking up,
     # the leftover split in two, the shortest quarter last), next to a sequence with a single block
     ("d128_two_way_walks", [(0, 1500, 0, 1500 + 200), (1500, 90, 1700, 90)], 64, 64, 128),
+    # 65 key blocks of context per key/value head: the equal walks of a queue start in three groups, one after the other
+    ("d128_context_in_groups", [(0, 200, 0, 200 + 65 * 128)], 8, 8, 128),
     # head_dim 256 (a variant of the path: other head dimensions)
     ("d256_one_token", [(0, 1, 0, 1)], 2, 2, 256),
     ("d256_ragged_tail_slice", [(0, 130, 0, 1000)], 8, 2, 256),
